@@ -1,0 +1,169 @@
+"""CPU oracle for the padding-free transformer-layer forward.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+file; the product path (the HIP library) never does, and this file imports nothing
+from it.  Everything is NumPy fp64 (plus scipy's erf), written for reading, not speed.
+
+What the method computes (Sec. 4.3, "Distributed Redundant Computation
+Elimination"): the tokens of a padded batch are gathered into one dense matrix,
+the position-wise operations run on that matrix, and the padded layout is rebuilt.
+A linear layer treats every token vector on its own, so this removal changes no
+valid token's value: the method's result IS the ordinary padded layer forward,
+restricted to the valid positions.  The oracle is therefore that plain definition:
+a pre-LayerNorm decoder block (Sec. 2.2: an attention module made of a pair of
+linear layers around multi-head attention with a causal mask, then an MLP module
+made of a pair of linear layers) evaluated at ALL B*S positions, pads included,
+with pad rows set to zero at the very end.
+
+Readings the paper leaves open, fixed here (the same ones the HIP path follows):
+  * pre-LN block, residual around each module, no LayerNorm after the stack;
+  * right padding: valid tokens of sequence b sit at positions 0 .. len[b]-1;
+  * query i may attend key j iff j <= i and j < len[b];
+  * LayerNorm: biased variance over the H features, eps inside the square root;
+  * GeLU in its exact erf form; softmax scale 1/sqrt(d);
+  * weights stored [out, in]; w_qkv rows are Q | K | V, head-major inside each;
+  * a missing out-proj / FC2 bias (None) means "no bias": the row-split shard of
+    Sec. 4.1.3 keeps only its partial sum, the cross-GPU accumulation is left out;
+  * rebuilt pad rows are exact zeros; packed order is batch-major, then position.
+
+Pins (tests/test_oracle_*.py): brute-force unbatched runs, padding invariance,
+hand-computed one-token/one-head values, position-0 closed form, uniform-attention
+closed form, identity block with zero output weights, and per-stage agreement with
+textbook library routines.  No function here is "parity unpinned".
+"""
+import numpy as np
+from scipy.special import erf as _erf
+
+
+# --------------------------------------------------------------------------- packing
+def pack_indices(lengths, S):
+    """Compaction of the valid-token mask (Sec. 4.3, removing padding).
+
+    The mask over the row-major [B, S] grid is m[b, s] = (s < len[b]).  Its exclusive
+    prefix sum gives every valid token its packed row; here that is written out as:
+    cu[b] = number of valid tokens before sequence b, idx[t] = flat padded position
+    of packed row t.  Returns (cu int32 [B+1], idx int32 [T])."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    B = lengths.shape[0]
+    mask = np.zeros((B, S), dtype=bool)
+    for b in range(B):
+        if lengths[b] < 0 or lengths[b] > S:
+            raise ValueError("length out of range")
+        for s in range(S):
+            mask[b, s] = s < lengths[b]
+    flat = mask.reshape(-1)
+    excl = np.cumsum(flat) - flat          # exclusive prefix sum of the 0/1 mask
+    T = int(flat.sum())
+    idx = np.empty(T, dtype=np.int32)
+    for p in range(B * S):
+        if flat[p]:
+            idx[excl[p]] = p
+    cu = np.zeros(B + 1, dtype=np.int32)
+    for b in range(B):
+        cu[b + 1] = cu[b] + lengths[b]
+    return cu, idx
+
+
+def pack(x_pad, lengths):
+    """Remove padding: [B, S, H] -> [T, H] in batch-major, position order."""
+    B, S, H = x_pad.shape
+    _, idx = pack_indices(lengths, S)
+    return x_pad.reshape(B * S, H)[idx].copy()
+
+
+def unpack(x_packed, lengths, S):
+    """Rebuild padding: [T, H] -> [B, S, H]; pad rows are zero."""
+    B = len(lengths)
+    H = x_packed.shape[1]
+    _, idx = pack_indices(lengths, S)
+    out = np.zeros((B * S, H), dtype=x_packed.dtype)
+    out[idx] = x_packed
+    return out.reshape(B, S, H)
+
+
+# --------------------------------------------------------------------------- stages
+def layer_norm(x, gamma, beta, eps):
+    """Per-row normalisation over the last axis (biased variance)."""
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * gamma + beta
+
+
+def gelu(z):
+    return 0.5 * z * (1.0 + _erf(z / np.sqrt(2.0)))
+
+
+def linear(x, w, b):
+    """y = x @ w^T (+ b); w is [out, in]."""
+    y = x @ w.T
+    if b is not None:
+        y = y + b
+    return y
+
+
+def masked_causal_attention(q, k, v, length, n_heads, head_dim):
+    """Multi-head attention for ONE sequence laid out [S, A] (A = nh*d), evaluated at
+    every one of the S positions.  Query i sees the key set
+    J(i) = { j : j <= i and j < length }; an empty set (length 0) gives a zero row."""
+    S = q.shape[0]
+    out = np.zeros_like(q)
+    scale = 1.0 / np.sqrt(float(head_dim))
+    j = np.arange(S)
+    for i in range(S):
+        J = j[(j <= i) & (j < length)]          # allowed keys of query i
+        if J.size == 0:
+            continue
+        for h in range(n_heads):
+            c0, c1 = h * head_dim, (h + 1) * head_dim
+            s = (k[J, c0:c1] @ q[i, c0:c1]) * scale
+            p = np.exp(s - s.max())
+            p = p / p.sum()
+            out[i, c0:c1] = p @ v[J, c0:c1]
+    return out
+
+
+def layer_forward_padded(x_pad, lengths, p, n_heads, head_dim, eps=1e-5, stages=None):
+    """One pre-LN decoder block on the padded batch [B, S, H]; every position is
+    computed (pads too), nothing is zeroed here.  If `stages` is a dict it receives
+    the intermediates (u, qkv, attn, y1, w, m), each [B, S, .]."""
+    x_pad = np.asarray(x_pad, dtype=np.float64)
+    B, S, H = x_pad.shape
+    A = n_heads * head_dim
+    f = lambda a: None if a is None else np.asarray(a, dtype=np.float64)
+    p = {k_: f(v_) for k_, v_ in p.items()}
+    y = np.empty_like(x_pad)
+    keep = {k_: [] for k_ in ("u", "qkv", "attn", "y1", "w", "m")}
+    for b in range(B):
+        x = x_pad[b]
+        u = layer_norm(x, p["ln1_g"], p["ln1_b"], eps)
+        qkv = linear(u, p["w_qkv"], p["b_qkv"])
+        q, k, v = qkv[:, 0:A], qkv[:, A:2 * A], qkv[:, 2 * A:3 * A]
+        attn = masked_causal_attention(q, k, v, int(lengths[b]), n_heads, head_dim)
+        y1 = x + linear(attn, p["w_o"], p["b_o"])
+        w = layer_norm(y1, p["ln2_g"], p["ln2_b"], eps)
+        m = gelu(linear(w, p["w_fc1"], p["b_fc1"]))
+        y[b] = y1 + linear(m, p["w_fc2"], p["b_fc2"])
+        for name, val in (("u", u), ("qkv", qkv), ("attn", attn), ("y1", y1), ("w", w), ("m", m)):
+            keep[name].append(val)
+    if stages is not None:
+        for name, vals in keep.items():
+            stages[name] = np.stack(vals)
+    return y
+
+
+def zero_pad_rows(y_pad, lengths):
+    out = y_pad.copy()
+    for b in range(out.shape[0]):
+        out[b, int(lengths[b]):, :] = 0.0
+    return out
+
+
+def stack_forward(x_pad, lengths, layer_params, n_heads, head_dim, eps=1e-5, stages=None):
+    """L blocks applied in turn to the padded batch, then pad rows set to zero: the
+    result the pack -> L x layer -> unpack pipeline must reproduce.  `stages`, if
+    given, receives the LAST layer's intermediates."""
+    y = np.asarray(x_pad, dtype=np.float64)
+    for li, p in enumerate(layer_params):
+        st = stages if (stages is not None and li == len(layer_params) - 1) else None
+        y = layer_forward_padded(y, lengths, p, n_heads, head_dim, eps, st)
+    return zero_pad_rows(y, lengths)
