@@ -1,0 +1,189 @@
+/*
+ * energon.h -- C ABI of the padding-free transformer-layer forward for MI355X (gfx950).
+ *
+ * The library implements the redundant-computation-elimination step of the paper
+ * (Sec. 4.3): the valid tokens of a padded batch [B, S, H] are compacted into a dense
+ * [T, H] matrix (T = sum of the sequence lengths), the whole decoder block (Sec. 2.2:
+ * attention module + MLP module, causal mask) runs on those T rows only, and the padded
+ * layout is rebuilt at the end.  Unlike the paper's design, attention also runs on the
+ * packed rows (each sequence over its real length), so a stack of L layers packs once
+ * and unpacks once.
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are DEVICE pointers, *_host are HOST pointers.  The caller
+ *     owns every buffer; the library allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it and the call returns without waiting; two calls on different
+ *     streams may run concurrently if their buffers do not overlap.
+ *   - Arguments are validated on the host BEFORE anything is enqueued; a call that
+ *     returns an error other than ENERGON_ERR_HIP has touched no device memory.
+ *   - Matrices are row-major and dense.  Weights are stored [out_features, in_features],
+ *     so both GEMM operands are contiguous along the reduction.
+ *   - Device pointers must be 16-byte aligned.  For a layer, H, A = n_heads*head_dim and F
+ *     must be multiples of 64 (bf16) or 4 (fp32).
+ *   - Sequences are right-padded: the valid tokens of sequence b are positions
+ *     0 .. len[b]-1.  0 <= len[b] <= S.  len[b] = 0 and T = 0 are legal.
+ *   - Packed order is batch-major then position: packed row cu[b] + s holds padded
+ *     position (b, s), where cu is the exclusive prefix sum of the lengths.
+ */
+#ifndef ENERGON_H_
+#define ENERGON_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ENERGON_OK = 0,
+  ENERGON_ERR_NULL = -1,        /* a required pointer is NULL                           */
+  ENERGON_ERR_SHAPE = -2,       /* a dimension is non-positive or violates divisibility */
+  ENERGON_ERR_LENGTH = -3,      /* some len[b] < 0 or > S, or sum(len) != T             */
+  ENERGON_ERR_CAPACITY = -4,    /* output / workspace too small                         */
+  ENERGON_ERR_ALIGN = -5,       /* a device pointer is not 16-byte aligned              */
+  ENERGON_ERR_UNSUPPORTED = -6, /* dtype / head_dim / epilogue not implemented          */
+  ENERGON_ERR_HIP = -7          /* the HIP runtime reported an error                    */
+} energon_status;
+
+typedef enum {
+  ENERGON_F32 = 0,  /* fp32 storage, fp32 arithmetic (vector ALU)                        */
+  ENERGON_BF16 = 1  /* bf16 storage, MFMA with fp32 accumulation, fp32 epilogues         */
+} energon_dtype;
+
+/* Geometry of ONE GPU's share of a layer.  For a tensor-parallel shard (Sec. 4.1.3) pass
+ * the local head count and local FFN width; hidden stays the full model width. */
+typedef struct {
+  int32_t hidden;   /* H  */
+  int32_t n_heads;  /* nh : heads on this GPU                     */
+  int32_t head_dim; /* d  : 64 or 128                             */
+  int32_t ffn;      /* F  : FFN width on this GPU                 */
+  float ln_eps;     /* added to the variance inside the sqrt      */
+  int32_t dtype;    /* energon_dtype of activations AND weights   */
+} EnergonLayerConfig;
+
+/* Device pointers to one layer's parameters, element type = config dtype, read-only.
+ * A = nh*d.  w_qkv rows are ordered Q | K | V, head-major inside each third.
+ * b_o and b_fc2 may be NULL (row-split shard: the bias belongs after the cross-GPU sum);
+ * b_qkv and b_fc1 may be NULL too (no bias). */
+typedef struct {
+  const void *ln1_g, *ln1_b; /* [H]            */
+  const void *w_qkv, *b_qkv; /* [3A, H], [3A]  */
+  const void *w_o, *b_o;     /* [H, A],  [H]   */
+  const void *ln2_g, *ln2_b; /* [H]            */
+  const void *w_fc1, *b_fc1; /* [F, H],  [F]   */
+  const void *w_fc2, *b_fc2; /* [H, F],  [H]   */
+} EnergonLayerWeights;
+
+/* Epilogues of energon_linear (what is fused after the contraction). */
+typedef enum {
+  ENERGON_EPI_BIAS = 0,          /* y = x W^T + b                       */
+  ENERGON_EPI_BIAS_GELU = 1,     /* y = GeLU(x W^T + b), exact erf form */
+  ENERGON_EPI_BIAS_RESIDUAL = 2  /* y = r + x W^T + b                   */
+} energon_epilogue;
+
+/* Sub-buffers of the layer workspace, in the order energon_workspace_layout reports them. */
+enum {
+  ENERGON_WS_U = 0,    /* [T, H]  LayerNorm-1 output          */
+  ENERGON_WS_QKV = 1,  /* [T, 3A] Q | K | V                   */
+  ENERGON_WS_ATTN = 2, /* [T, A]  attention output            */
+  ENERGON_WS_Y1 = 3,   /* [T, H]  x + out-proj                */
+  ENERGON_WS_W = 4,    /* [T, H]  LayerNorm-2 output          */
+  ENERGON_WS_M = 5,    /* [T, F]  GeLU(FC1)                   */
+  ENERGON_WS_COUNT = 6
+};
+
+/* Stages timed by energon_layer_forward_profiled, in launch order. */
+enum {
+  ENERGON_STAGE_LN1 = 0, ENERGON_STAGE_QKV = 1, ENERGON_STAGE_ATTN = 2, ENERGON_STAGE_OUT = 3,
+  ENERGON_STAGE_LN2 = 4, ENERGON_STAGE_FC1 = 5, ENERGON_STAGE_FC2 = 6, ENERGON_STAGE_COUNT = 7
+};
+
+const char* energon_strerror(int status);
+
+/* Bytes of workspace energon_layer_forward needs for up to max_tokens packed rows.
+ * Returns 0 if cfg is NULL/invalid or max_tokens < 0. */
+size_t energon_workspace_bytes(const EnergonLayerConfig* cfg, int64_t max_tokens);
+
+/* Byte offsets (offsets_out[ENERGON_WS_COUNT], host) at which a call of
+ * energon_layer_forward with exactly `tokens` packed rows places its intermediates inside
+ * the workspace; they stay there until the next call (for tests and debugging). */
+int energon_workspace_layout(const EnergonLayerConfig* cfg, int64_t tokens, size_t* offsets_out);
+
+/* Remove padding (Sec. 4.3).  Computes on the device, with a wavefront prefix scan,
+ * cu_seqlens_dev[B+1] (exclusive prefix sum of lengths, cu[B] = T) and gathers the valid
+ * rows:  x_packed[cu[b]+s, :] = x_padded[b, s, :],  token_idx_dev[cu[b]+s] = b*S + s.
+ *   x_padded_dev   [B, S, H]   in
+ *   lengths_host   [B]         in, host; copied before return, reusable afterwards
+ *   x_packed_dev   [capacity_tokens, H] out; rows >= T are left untouched
+ *   cu_seqlens_dev [B+1] int32 out;  token_idx_dev [capacity_tokens] int32 out (first T)
+ *   total_tokens_out           host, optional: T, computed on the host (no device sync)
+ * Errors: NULL, SHAPE (B,S,H <= 0, H not a multiple of 8 (4 for fp32), B*S >= 2^31),
+ * LENGTH, CAPACITY (T > capacity_tokens), ALIGN, UNSUPPORTED (dtype), HIP. */
+int energon_pack(const void* x_padded_dev, const int32_t* lengths_host, int32_t B, int32_t S,
+                 int32_t H, int32_t dtype, void* x_packed_dev, int64_t capacity_tokens,
+                 int32_t* cu_seqlens_dev, int32_t* token_idx_dev, int64_t* total_tokens_out,
+                 void* stream);
+
+/* Rebuild padding (Sec. 4.3).  y_padded[b, s, :] = y_packed[cu[b]+s, :] for s < len[b],
+ * exact zeros elsewhere; every element of y_padded is written exactly once.
+ *   y_packed_dev [T, H] in; cu_seqlens_dev [B+1] in (as written by energon_pack);
+ *   y_padded_dev [B, S, H] out.  T is only used for validation (0 <= T <= B*S). */
+int energon_unpack(const void* y_packed_dev, const int32_t* cu_seqlens_dev, int64_t T, int32_t B,
+                   int32_t S, int32_t H, int32_t dtype, void* y_padded_dev, void* stream);
+
+/* One pre-LN decoder block (Sec. 2.2) on T packed rows:
+ *   u = LN1(x); qkv = u Wqkv^T + bqkv; a = causal attention of each sequence over its own
+ *   len[b] tokens; y1 = x + a Wo^T + bo; w = LN2(y1); m = GeLU(w W1^T + b1);
+ *   y = y1 + m W2^T + b2.
+ *   x_packed_dev [T, H] in; y_packed_dev [T, H] out (may be the same buffer as x);
+ *   cu_seqlens_dev [B+1] in; lengths_host [B] in (host; used for validation and launch
+ *   shapes only: sum must equal T, each 0 <= len <= max_len);
+ *   workspace_dev: at least energon_workspace_bytes(cfg, T) bytes, 256-byte aligned.
+ * Errors: NULL, SHAPE (dims <= 0, H/A/F not multiples of 4 (bf16: of 64)),
+ * LENGTH, CAPACITY (workspace), ALIGN, UNSUPPORTED (head_dim not 64/128, dtype), HIP. */
+int energon_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* weights,
+                          const void* x_packed_dev, void* y_packed_dev, int64_t T,
+                          const int32_t* cu_seqlens_dev, const int32_t* lengths_host, int32_t B,
+                          int32_t max_len, void* workspace_dev, size_t workspace_bytes,
+                          void* stream);
+
+/* Same work as energon_layer_forward, with a HIP event recorded on `stream` between the
+ * stages; waits for the stream and writes the elapsed milliseconds of each stage to
+ * stage_ms_host[ENERGON_STAGE_COUNT].  A measurement aid: it creates and destroys events
+ * and blocks the caller. */
+int energon_layer_forward_profiled(const EnergonLayerConfig* cfg,
+                                   const EnergonLayerWeights* weights, const void* x_packed_dev,
+                                   void* y_packed_dev, int64_t T, const int32_t* cu_seqlens_dev,
+                                   const int32_t* lengths_host, int32_t B, int32_t max_len,
+                                   void* workspace_dev, size_t workspace_bytes, void* stream,
+                                   float* stage_ms_host);
+
+/* ---- the stages on their own (same kernels energon_layer_forward launches) ---------- */
+
+/* Row-wise LayerNorm over H features: y = (x-mean)/sqrt(var+eps)*gamma+beta, biased
+ * variance, statistics in fp32.  x_dev, y_dev [T, H]; gamma_dev, beta_dev [H]. */
+int energon_layernorm(const void* x_dev, const void* gamma_dev, const void* beta_dev, void* y_dev,
+                      int64_t T, int32_t H, float eps, int32_t dtype, void* stream);
+
+/* y[M, N] = epilogue(x[M, K] W[N, K]^T + bias[N]) with residual r[M, N] for
+ * ENERGON_EPI_BIAS_RESIDUAL (r may be the same buffer as y).  bias_dev may be NULL.
+ * bf16: MFMA, fp32 accumulation, epilogue in fp32, one rounding to bf16 on store;
+ * needs K % 64 == 0 and N % 8 == 0.  fp32: N % 4 == 0, K % 4 == 0. */
+int energon_linear(const void* x_dev, const void* w_dev, const void* bias_dev,
+                   const void* residual_dev, void* y_dev, int64_t M, int32_t N, int32_t K,
+                   int32_t epilogue, int32_t dtype, void* stream);
+
+/* Causal attention of every sequence over its real length, on packed rows.
+ *   qkv_dev [T, 3A]  (row t: Q | K | V, head h at columns h*d .. (h+1)*d-1 of each third)
+ *   out_dev [T, A];  cu_seqlens_dev [B+1];  max_len >= every sequence length.
+ * o_i = sum_{j<=i} softmax_j(q_i.k_j / sqrt(d)) v_j with i, j inside one sequence. */
+int energon_attention(const void* qkv_dev, void* out_dev, const int32_t* cu_seqlens_dev,
+                      int64_t T, int32_t B, int32_t max_len, int32_t n_heads, int32_t head_dim,
+                      int32_t dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENERGON_H_ */

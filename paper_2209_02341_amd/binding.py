@@ -1,0 +1,192 @@
+"""ctypes binding of libenergon.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  Tensors are torch tensors used
+as typed device memory (data_ptr) and the stream is torch's current HIP stream; nothing is
+computed here.  If the library has not been built, importing a function fails loudly:
+there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libenergon.so")
+
+F32, BF16 = 0, 1
+EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL = 0, 1, 2
+WS_U, WS_QKV, WS_ATTN, WS_Y1, WS_W, WS_M, WS_COUNT = 0, 1, 2, 3, 4, 5, 6
+STAGE_NAMES = ("ln1", "qkv", "attn", "out", "ln2", "fc1", "fc2")
+
+
+class EnergonError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status} ({strerror(status)})")
+
+
+class LayerConfig(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("ln_eps", C.c_float), ("dtype", C.c_int32)]
+
+
+_WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b",
+                  "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it was not built (python -m paper_2209_02341_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with __graft_entry__.build(); "
+                               "there is no fallback path")
+        l = C.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        pcfg, pw = C.POINTER(LayerConfig), C.POINTER(LayerWeights)
+        l.energon_strerror.restype = C.c_char_p
+        l.energon_strerror.argtypes = [C.c_int]
+        l.energon_workspace_bytes.restype = sz
+        l.energon_workspace_bytes.argtypes = [pcfg, i64]
+        l.energon_workspace_layout.argtypes = [pcfg, i64, C.POINTER(sz)]
+        l.energon_pack.argtypes = [vp, vp, i32, i32, i32, i32, vp, i64, vp, vp, C.POINTER(i64), vp]
+        l.energon_unpack.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp]
+        layer_args = [pcfg, pw, vp, vp, i64, vp, vp, i32, i32, vp, sz, vp]
+        l.energon_layer_forward.argtypes = layer_args
+        l.energon_layer_forward_profiled.argtypes = layer_args + [C.POINTER(C.c_float)]
+        l.energon_layernorm.argtypes = [vp, vp, vp, vp, i64, i32, C.c_float, i32, vp]
+        l.energon_linear.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
+        l.energon_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+        for name in ("energon_workspace_layout", "energon_pack", "energon_unpack", "energon_layer_forward",
+                     "energon_layer_forward_profiled", "energon_layernorm", "energon_linear",
+                     "energon_attention"):
+            getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / raw int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+
+
+def _lengths(lengths) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(lengths), dtype=np.int32)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise EnergonError(status, where)
+
+
+def make_weights(tensors: dict) -> LayerWeights:
+    """LayerWeights from a dict of device tensors (missing / None bias = NULL).  The caller
+    keeps the tensors alive."""
+    w = LayerWeights()
+    for n in _WEIGHT_FIELDS:
+        setattr(w, n, _ptr(tensors.get(n)))
+    return w
+
+
+# ------------------------------------------------------------------ the C ABI, same names
+def strerror(status: int) -> str:
+    return lib().energon_strerror(int(status)).decode()
+
+
+def energon_workspace_bytes(cfg: LayerConfig, max_tokens: int) -> int:
+    return int(lib().energon_workspace_bytes(C.byref(cfg), int(max_tokens)))
+
+
+def energon_workspace_layout(cfg: LayerConfig, max_tokens: int) -> list:
+    off = (C.c_size_t * WS_COUNT)()
+    _check(lib().energon_workspace_layout(C.byref(cfg), int(max_tokens), off), "energon_workspace_layout")
+    return [int(v) for v in off]
+
+
+def energon_pack(x_padded, lengths, x_packed, cu_seqlens, token_idx, stream=None) -> int:
+    """x_padded [B,S,H] device; lengths host int32 [B]; outputs device.  Returns T."""
+    B, S, H = x_padded.shape
+    lens = _lengths(lengths)
+    total = C.c_int64(-1)
+    _check(lib().energon_pack(_ptr(x_padded), _ptr(lens), B, S, H, _dtype_code(x_padded), _ptr(x_packed),
+                              int(x_packed.shape[0]), _ptr(cu_seqlens), _ptr(token_idx), C.byref(total),
+                              _stream(stream)), "energon_pack")
+    return int(total.value)
+
+
+def energon_unpack(y_packed, cu_seqlens, T: int, y_padded, stream=None) -> None:
+    B, S, H = y_padded.shape
+    _check(lib().energon_unpack(_ptr(y_packed), _ptr(cu_seqlens), int(T), B, S, H, _dtype_code(y_padded),
+                                _ptr(y_padded), _stream(stream)), "energon_unpack")
+
+
+def energon_layer_forward(cfg: LayerConfig, weights: LayerWeights, x_packed, y_packed, T: int, cu_seqlens,
+                          lengths, max_len: int, workspace, stream=None) -> None:
+    lens = _lengths(lengths)
+    _check(lib().energon_layer_forward(C.byref(cfg), C.byref(weights), _ptr(x_packed), _ptr(y_packed), int(T),
+                                       _ptr(cu_seqlens), _ptr(lens), len(lens), int(max_len), _ptr(workspace),
+                                       int(workspace.numel() * workspace.element_size()), _stream(stream)),
+           "energon_layer_forward")
+
+
+def energon_layer_forward_profiled(cfg: LayerConfig, weights: LayerWeights, x_packed, y_packed, T: int,
+                                   cu_seqlens, lengths, max_len: int, workspace, stream=None) -> dict:
+    lens = _lengths(lengths)
+    ms = (C.c_float * len(STAGE_NAMES))()
+    _check(lib().energon_layer_forward_profiled(C.byref(cfg), C.byref(weights), _ptr(x_packed), _ptr(y_packed),
+                                                int(T), _ptr(cu_seqlens), _ptr(lens), len(lens), int(max_len),
+                                                _ptr(workspace),
+                                                int(workspace.numel() * workspace.element_size()),
+                                                _stream(stream), ms), "energon_layer_forward_profiled")
+    return dict(zip(STAGE_NAMES, (float(v) for v in ms)))
+
+
+def energon_layernorm(x, gamma, beta, y, eps: float, stream=None) -> None:
+    T, H = x.shape
+    _check(lib().energon_layernorm(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), T, H, float(eps), _dtype_code(x),
+                                   _stream(stream)), "energon_layernorm")
+
+
+def energon_linear(x, w, bias, residual, y, epilogue: int, stream=None) -> None:
+    M, K = x.shape
+    N = w.shape[0]
+    _check(lib().energon_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K, int(epilogue),
+                                _dtype_code(x), _stream(stream)), "energon_linear")
+
+
+def energon_attention(qkv, out, cu_seqlens, B: int, max_len: int, n_heads: int, head_dim: int,
+                      stream=None) -> None:
+    T = qkv.shape[0]
+    _check(lib().energon_attention(_ptr(qkv), _ptr(out), _ptr(cu_seqlens), T, int(B), int(max_len), int(n_heads),
+                                   int(head_dim), _dtype_code(qkv), _stream(stream)), "energon_attention")

@@ -1,0 +1,69 @@
+// Shared device helpers and the launch functions each kernel file exports.
+// gfx950 only: 64-lane wavefronts, bf16 MFMA, hardware bf16 conversion.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace energon {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// Element traits: VEC elements make one 16-byte vector.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int VEC = 4;
+  __device__ static inline float to_f32(float v) { return v; }
+  __device__ static inline float from_f32(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int VEC = 8;
+  __device__ static inline float to_f32(bf16_t v) { return static_cast<float>(v); }
+  __device__ static inline bf16_t from_f32(float v) { return static_cast<bf16_t>(v); }  // RNE
+};
+
+template <typename T> struct alignas(16) Vec16 { T v[Elem<T>::VEC]; };
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Exact GeLU, z * Phi(z), in fp32.
+__device__ inline float gelu_erf(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+
+enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2 };
+
+// ---- launchers (each returns the hipError_t of its launch) --------------------------------
+// pack.hip
+hipError_t launch_scan_lengths(int32_t* cu_seqlens, int32_t B, hipStream_t s);
+hipError_t launch_pack_rows(const void* x_padded, void* x_packed, const int32_t* cu, int32_t* token_idx,
+                            int32_t B, int32_t S, int64_t row_bytes, int64_t T, hipStream_t s);
+hipError_t launch_unpack_rows(const void* y_packed, void* y_padded, const int32_t* cu, int32_t B, int32_t S,
+                              int64_t row_bytes, hipStream_t s);
+// layernorm.hip
+hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t T, int32_t H,
+                            float eps, bool bf16, hipStream_t s);
+// gemm_f32.hip / gemm_bf16.hip
+hipError_t launch_gemm_f32(const float* x, const float* w, const float* bias, const float* res, float* y,
+                           int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
+hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
+                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
+// attention_f32.hip / attention_bf16.hip
+hipError_t launch_attention_f32(const float* qkv, float* out, const int32_t* cu, int32_t B, int32_t max_len,
+                                int32_t nh, int32_t d, hipStream_t s);
+hipError_t launch_attention_bf16(const bf16_t* qkv, bf16_t* out, const int32_t* cu, int32_t B, int32_t max_len,
+                                 int32_t nh, int32_t d, hipStream_t s);
+
+}  // namespace energon

@@ -1,0 +1,272 @@
+// C ABI of the library (see include/energon.h): argument validation on the host, then
+// the kernel launches of each stage, all on the caller's stream.  No allocation, no state.
+#include "../../include/energon.h"
+#include "common.h"
+
+using namespace energon;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int esize(int32_t dt) { return dt == ENERGON_BF16 ? 2 : 4; }
+inline int vec_elems(int32_t dt) { return dt == ENERGON_BF16 ? 8 : 4; }
+inline bool dtype_ok(int32_t dt) { return dt == ENERGON_F32 || dt == ENERGON_BF16; }
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ENERGON_ERR_HIP; } while (0)
+
+int check_cfg(const EnergonLayerConfig* c) {
+  if (!c) return ENERGON_ERR_NULL;
+  if (!dtype_ok(c->dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (c->hidden <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->ffn <= 0) return ENERGON_ERR_SHAPE;
+  if (c->head_dim != 64 && c->head_dim != 128) return ENERGON_ERR_UNSUPPORTED;
+  const int64_t A = (int64_t)c->n_heads * c->head_dim;
+  if (A > (1 << 28) || c->hidden > (1 << 28) || c->ffn > (1 << 28)) return ENERGON_ERR_SHAPE;
+  // bf16: every reduction dimension (H, A, F) is walked in 64-element slabs by the MFMA GEMM
+  const int div = c->dtype == ENERGON_BF16 ? 64 : 4;
+  if (c->hidden % div || A % div || c->ffn % div) return ENERGON_ERR_SHAPE;
+  if (!(c->ln_eps >= 0.f)) return ENERGON_ERR_SHAPE;
+  return ENERGON_OK;
+}
+
+// T must equal the sum; every length within [0, max_len]
+int check_lengths(const int32_t* lengths, int32_t B, int32_t max_len, int64_t* total) {
+  int64_t t = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    if (lengths[b] < 0 || lengths[b] > max_len) return ENERGON_ERR_LENGTH;
+    t += lengths[b];
+  }
+  *total = t;
+  return ENERGON_OK;
+}
+
+struct WsLayout { size_t off[ENERGON_WS_COUNT]; size_t total; };
+
+WsLayout ws_layout(const EnergonLayerConfig* c, int64_t T) {
+  const size_t e = esize(c->dtype), t = (size_t)T;
+  const size_t A = (size_t)c->n_heads * c->head_dim, H = c->hidden, F = c->ffn;
+  const size_t sizes[ENERGON_WS_COUNT] = {t * H * e, t * 3 * A * e, t * A * e, t * H * e, t * H * e, t * F * e};
+  WsLayout l;
+  size_t o = 0;
+  for (int i = 0; i < ENERGON_WS_COUNT; ++i) { l.off[i] = o; o += round256(sizes[i]); }
+  l.total = o;
+  return l;
+}
+
+int linear_impl(const void* x, const void* w, const void* bias, const void* res, void* y, int64_t M, int32_t N,
+                int32_t K, int32_t epi, int32_t dt, hipStream_t s) {
+  if (dt == ENERGON_BF16)
+    HIP_TRY(launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, (const bf16_t*)res, (bf16_t*)y,
+                             M, N, K, epi, s));
+  else
+    HIP_TRY(launch_gemm_f32((const float*)x, (const float*)w, (const float*)bias, (const float*)res, (float*)y, M, N,
+                            K, epi, s));
+  return ENERGON_OK;
+}
+
+int attention_impl(const void* qkv, void* out, const int32_t* cu, int32_t B, int32_t max_len, int32_t nh, int32_t d,
+                   int32_t dt, hipStream_t s) {
+  if (dt == ENERGON_BF16)
+    HIP_TRY(launch_attention_bf16((const bf16_t*)qkv, (bf16_t*)out, cu, B, max_len, nh, d, s));
+  else
+    HIP_TRY(launch_attention_f32((const float*)qkv, (float*)out, cu, B, max_len, nh, d, s));
+  return ENERGON_OK;
+}
+
+int check_layer_args(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y, int64_t T,
+                     const int32_t* cu, const int32_t* lengths, int32_t B, int32_t max_len, void* ws,
+                     size_t ws_bytes) {
+  int st = check_cfg(cfg);
+  if (st != ENERGON_OK) return st;
+  if (!w || !x || !y || !cu || !lengths || !ws) return ENERGON_ERR_NULL;
+  if (!w->ln1_g || !w->ln1_b || !w->w_qkv || !w->w_o || !w->ln2_g || !w->ln2_b || !w->w_fc1 || !w->w_fc2)
+    return ENERGON_ERR_NULL;
+  if (B <= 0 || B > 65535 || max_len <= 0 || T < 0) return ENERGON_ERR_SHAPE;
+  int64_t total = 0;
+  st = check_lengths(lengths, B, max_len, &total);
+  if (st != ENERGON_OK) return st;
+  if (total != T) return ENERGON_ERR_LENGTH;
+  if (T >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
+  const void* ptrs[] = {x, y, ws, w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o, w->b_o,
+                        w->ln2_g, w->ln2_b, w->w_fc1, w->b_fc1, w->w_fc2, w->b_fc2};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ENERGON_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return ENERGON_ERR_ALIGN;
+  if (ws_bytes < ws_layout(cfg, T).total) return ENERGON_ERR_CAPACITY;
+  return ENERGON_OK;
+}
+
+// The block itself.  ev == nullptr: plain launches; otherwise ev[0..STAGE_COUNT] are recorded
+// around the stages.
+int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y, int64_t T,
+               const int32_t* cu, int32_t B, int32_t max_len, void* ws, hipStream_t s, hipEvent_t* ev) {
+  const WsLayout l = ws_layout(cfg, T);
+  char* base = static_cast<char*>(ws);
+  void* u = base + l.off[ENERGON_WS_U];
+  void* qkv = base + l.off[ENERGON_WS_QKV];
+  void* att = base + l.off[ENERGON_WS_ATTN];
+  void* y1 = base + l.off[ENERGON_WS_Y1];
+  void* wn = base + l.off[ENERGON_WS_W];
+  void* m = base + l.off[ENERGON_WS_M];
+  const int32_t H = cfg->hidden, A = cfg->n_heads * cfg->head_dim, F = cfg->ffn, dt = cfg->dtype;
+  const bool bf = dt == ENERGON_BF16;
+  int st;
+#define MARK(i) do { if (ev) HIP_TRY(hipEventRecord(ev[i], s)); } while (0)
+#define STEP(call) do { st = (call); if (st != ENERGON_OK) return st; } while (0)
+  MARK(0);
+  HIP_TRY(launch_layernorm(x, w->ln1_g, w->ln1_b, u, T, H, cfg->ln_eps, bf, s));
+  MARK(1);
+  STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, T, 3 * A, H, ENERGON_EPI_BIAS, dt, s));
+  MARK(2);
+  if (T > 0) STEP(attention_impl(qkv, att, cu, B, max_len, cfg->n_heads, cfg->head_dim, dt, s));
+  MARK(3);
+  STEP(linear_impl(att, w->w_o, w->b_o, x, y1, T, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+  MARK(4);
+  HIP_TRY(launch_layernorm(y1, w->ln2_g, w->ln2_b, wn, T, H, cfg->ln_eps, bf, s));
+  MARK(5);
+  STEP(linear_impl(wn, w->w_fc1, w->b_fc1, nullptr, m, T, F, H, ENERGON_EPI_BIAS_GELU, dt, s));
+  MARK(6);
+  STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, T, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+  MARK(7);
+#undef MARK
+#undef STEP
+  return ENERGON_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* energon_strerror(int status) {
+  switch (status) {
+    case ENERGON_OK: return "ok";
+    case ENERGON_ERR_NULL: return "a required pointer is NULL";
+    case ENERGON_ERR_SHAPE: return "a dimension is non-positive, too large, or violates a divisibility rule";
+    case ENERGON_ERR_LENGTH: return "a sequence length is outside [0, S] or the lengths do not sum to T";
+    case ENERGON_ERR_CAPACITY: return "an output buffer or the workspace is too small";
+    case ENERGON_ERR_ALIGN: return "a device pointer is not aligned as required";
+    case ENERGON_ERR_UNSUPPORTED: return "unsupported dtype, head_dim, epilogue or batch size";
+    case ENERGON_ERR_HIP: return "the HIP runtime reported an error";
+    default: return "unknown status";
+  }
+}
+
+size_t energon_workspace_bytes(const EnergonLayerConfig* cfg, int64_t max_tokens) {
+  if (check_cfg(cfg) != ENERGON_OK || max_tokens < 0) return 0;
+  const size_t t = ws_layout(cfg, max_tokens).total;
+  return t ? t : 256;
+}
+
+int energon_workspace_layout(const EnergonLayerConfig* cfg, int64_t max_tokens, size_t* offsets_out) {
+  const int st = check_cfg(cfg);
+  if (st != ENERGON_OK) return st;
+  if (!offsets_out) return ENERGON_ERR_NULL;
+  if (max_tokens < 0) return ENERGON_ERR_SHAPE;
+  const WsLayout l = ws_layout(cfg, max_tokens);
+  for (int i = 0; i < ENERGON_WS_COUNT; ++i) offsets_out[i] = l.off[i];
+  return ENERGON_OK;
+}
+
+int energon_pack(const void* x_padded, const int32_t* lengths, int32_t B, int32_t S, int32_t H, int32_t dtype,
+                 void* x_packed, int64_t capacity_tokens, int32_t* cu, int32_t* token_idx, int64_t* total_out,
+                 void* stream) {
+  if (!x_padded || !lengths || !x_packed || !cu || !token_idx) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (B <= 0 || S <= 0 || H <= 0 || H % vec_elems(dtype) != 0 || capacity_tokens < 0) return ENERGON_ERR_SHAPE;
+  if ((int64_t)B * S >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
+  int64_t T = 0;
+  const int st = check_lengths(lengths, B, S, &T);
+  if (st != ENERGON_OK) return st;
+  if (T > capacity_tokens) return ENERGON_ERR_CAPACITY;
+  if (!aligned16(x_padded) || !aligned16(x_packed) || (reinterpret_cast<uintptr_t>(cu) & 3u) ||
+      (reinterpret_cast<uintptr_t>(token_idx) & 3u))
+    return ENERGON_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // lengths land in cu[1..B]; the scan kernel turns them into the prefix sums in place
+  HIP_TRY(hipMemcpyAsync(cu + 1, lengths, sizeof(int32_t) * (size_t)B, hipMemcpyHostToDevice, s));
+  HIP_TRY(launch_scan_lengths(cu, B, s));
+  HIP_TRY(launch_pack_rows(x_padded, x_packed, cu, token_idx, B, S, (int64_t)H * esize(dtype), T, s));
+  if (total_out) *total_out = T;
+  return ENERGON_OK;
+}
+
+int energon_unpack(const void* y_packed, const int32_t* cu, int64_t T, int32_t B, int32_t S, int32_t H,
+                   int32_t dtype, void* y_padded, void* stream) {
+  if (!y_packed || !cu || !y_padded) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (B <= 0 || S <= 0 || H <= 0 || H % vec_elems(dtype) != 0) return ENERGON_ERR_SHAPE;
+  if ((int64_t)B * S >= ((int64_t)1 << 31) || T < 0 || T > (int64_t)B * S) return ENERGON_ERR_SHAPE;
+  if (!aligned16(y_packed) || !aligned16(y_padded) || (reinterpret_cast<uintptr_t>(cu) & 3u)) return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_unpack_rows(y_packed, y_padded, cu, B, S, (int64_t)H * esize(dtype), static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y,
+                          int64_t T, const int32_t* cu, const int32_t* lengths, int32_t B, int32_t max_len, void* ws,
+                          size_t ws_bytes, void* stream) {
+  const int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
+  if (st != ENERGON_OK) return st;
+  return layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, static_cast<hipStream_t>(stream), nullptr);
+}
+
+int energon_layer_forward_profiled(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x,
+                                   void* y, int64_t T, const int32_t* cu, const int32_t* lengths, int32_t B,
+                                   int32_t max_len, void* ws, size_t ws_bytes, void* stream, float* stage_ms) {
+  if (!stage_ms) return ENERGON_ERR_NULL;
+  int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
+  if (st != ENERGON_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t ev[ENERGON_STAGE_COUNT + 1];
+  int made = 0;
+  for (; made <= ENERGON_STAGE_COUNT; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) break;
+  if (made <= ENERGON_STAGE_COUNT) {
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return ENERGON_ERR_HIP;
+  }
+  st = layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, s, ev);
+  if (st == ENERGON_OK && hipEventSynchronize(ev[ENERGON_STAGE_COUNT]) != hipSuccess) st = ENERGON_ERR_HIP;
+  if (st == ENERGON_OK)
+    for (int i = 0; i < ENERGON_STAGE_COUNT; ++i)
+      if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = ENERGON_ERR_HIP;
+  if (st != ENERGON_OK) (void)hipStreamSynchronize(s);
+  for (int i = 0; i <= ENERGON_STAGE_COUNT; ++i) (void)hipEventDestroy(ev[i]);
+  return st;
+}
+
+int energon_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t T, int32_t H, float eps,
+                      int32_t dtype, void* stream) {
+  if (!x || !gamma || !beta || !y) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (T < 0 || T >= ((int64_t)1 << 31) || H <= 0 || H % vec_elems(dtype) != 0 || !(eps >= 0.f)) return ENERGON_ERR_SHAPE;
+  if (H / vec_elems(dtype) > 256 * 16) return ENERGON_ERR_UNSUPPORTED;
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y)) return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_layernorm(x, gamma, beta, y, T, H, eps, dtype == ENERGON_BF16, static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_linear(const void* x, const void* w, const void* bias, const void* residual, void* y, int64_t M,
+                   int32_t N, int32_t K, int32_t epilogue, int32_t dtype, void* stream) {
+  if (!x || !w || !y) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (epilogue < ENERGON_EPI_BIAS || epilogue > ENERGON_EPI_BIAS_RESIDUAL) return ENERGON_ERR_UNSUPPORTED;
+  if (epilogue == ENERGON_EPI_BIAS_RESIDUAL && !residual) return ENERGON_ERR_NULL;
+  if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0) return ENERGON_ERR_SHAPE;
+  if (dtype == ENERGON_BF16 ? (K % 64 != 0 || N % 8 != 0) : (K % 4 != 0 || N % 4 != 0)) return ENERGON_ERR_SHAPE;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(y))
+    return ENERGON_ERR_ALIGN;
+  return linear_impl(x, w, bias, residual, y, M, N, K, epilogue, dtype, static_cast<hipStream_t>(stream));
+}
+
+int energon_attention(const void* qkv, void* out, const int32_t* cu, int64_t T, int32_t B, int32_t max_len,
+                      int32_t n_heads, int32_t head_dim, int32_t dtype, void* stream) {
+  if (!qkv || !out || !cu) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (head_dim != 64 && head_dim != 128) return ENERGON_ERR_UNSUPPORTED;
+  if (B <= 0 || max_len <= 0 || n_heads <= 0 || T < 0 || T >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
+  if (B > 65535 || n_heads > 65535) return ENERGON_ERR_UNSUPPORTED;
+  if (!aligned16(qkv) || !aligned16(out) || (reinterpret_cast<uintptr_t>(cu) & 3u)) return ENERGON_ERR_ALIGN;
+  if (T == 0) return ENERGON_OK;
+  return attention_impl(qkv, out, cu, B, max_len, n_heads, head_dim, dtype, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+"""Device-side plumbing shared by the GPU tests, the smoke check and the benchmark:
+uploading a synthetic workload, allocating the buffers the C ABI wants, and calling
+pack -> L x layer_forward -> unpack.  torch is used for device memory only."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as E
+from . import workloads as wl
+
+
+def to_device(a: np.ndarray | None, dtype: str, device="cuda"):
+    """fp32 host array (already rounded to `dtype`) -> device tensor of that dtype."""
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == wl.BF16:
+        bits = wl.f32_to_bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """device tensor -> fp64 host array (exact)."""
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def layer_config(hidden, n_heads, head_dim, ffn, dtype: str, eps=1e-5) -> E.LayerConfig:
+    return E.LayerConfig(hidden, n_heads, head_dim, ffn, eps, E.BF16 if dtype == wl.BF16 else E.F32)
+
+
+class DeviceLayer:
+    """One layer's parameters on the device plus the pointer struct handed to the library."""
+
+    def __init__(self, params: dict, dtype: str, device="cuda"):
+        self.tensors = {k: to_device(v, dtype, device) for k, v in params.items()}
+        self.struct = E.make_weights(self.tensors)
+
+
+class PackedRun:
+    """Buffers for one batch: packed activations (ping/pong), cu_seqlens, token_idx, workspace."""
+
+    def __init__(self, cfg: E.LayerConfig, B: int, S: int, capacity_tokens: int, device="cuda"):
+        tdt = torch.bfloat16 if cfg.dtype == E.BF16 else torch.float32
+        cap = max(int(capacity_tokens), 1)
+        self.cfg, self.B, self.S = cfg, B, S
+        self.x_packed = torch.empty((cap, cfg.hidden), dtype=tdt, device=device)
+        self.y_packed = torch.empty((cap, cfg.hidden), dtype=tdt, device=device)
+        self.cu = torch.empty(B + 1, dtype=torch.int32, device=device)
+        self.idx = torch.empty(cap, dtype=torch.int32, device=device)
+        self.ws_bytes = E.energon_workspace_bytes(cfg, cap)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        self.y_padded = torch.empty((B, S, cfg.hidden), dtype=tdt, device=device)
+        self.T = 0
+
+    def forward(self, x_padded: torch.Tensor, lengths: np.ndarray, layers: list) -> torch.Tensor:
+        """pack once, every layer on the packed rows, unpack once; returns y_padded."""
+        cfg = self.cfg
+        self.T = T = E.energon_pack(x_padded, lengths, self.x_packed, self.cu, self.idx)
+        src, dst = self.x_packed, self.y_packed
+        for layer in layers:
+            E.energon_layer_forward(cfg, layer.struct, src, dst, T, self.cu, lengths, self.S, self.workspace)
+            src, dst = dst, src
+        self.last_packed = src
+        E.energon_unpack(src, self.cu, T, self.y_padded)
+        return self.y_padded
+
+    def stage(self, which: int, cols: int) -> torch.Tensor:
+        """View of one intermediate of the last layer run, [T, cols]."""
+        off = E.energon_workspace_layout(self.cfg, self.T)[which]
+        esz = self.x_packed.element_size()
+        flat = self.workspace[off: off + self.T * cols * esz]
+        return flat.view(self.x_packed.dtype).view(self.T, cols)

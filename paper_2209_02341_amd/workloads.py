@@ -7,16 +7,18 @@ Sec. 5.5: batches whose valid length is a fraction of the padded length).  It
 holds none of the method's arithmetic (no LayerNorm, GEMM, attention, scan); both
 the CPU oracle's tests and the GPU harness consume its output as plain arrays.
 
-Every tensor has its own counter-free random stream keyed by
-(seed, tensor name, layer), so any tensor can be regenerated alone, in any order.
+Every tensor has its own random streams keyed by (seed, tensor name, layer, row chunk),
+so any tensor can be regenerated alone, in any order, on any number of threads.
 Values are drawn in fp32 and, for bf16 workloads, rounded to bf16 (round to
 nearest even) once here; the oracle and the GPU path both start from those
 rounded values.
 """
 from __future__ import annotations
 
+import os
 import zlib
-from dataclasses import dataclass, field
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
 
 import numpy as np
 
@@ -65,9 +67,9 @@ WORKLOADS = {
 }
 
 
-def _stream(seed: int, name: str, layer: int = 0) -> np.random.Generator:
+def _stream(seed: int, name: str, layer: int = 0, chunk: int = 0) -> np.random.Generator:
     key = zlib.crc32(name.encode("ascii"))
-    return np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, key, layer])))
+    return np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, key, layer, chunk])))
 
 
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
@@ -103,14 +105,30 @@ def sample_lengths(w: Workload, seed: int = 0) -> np.ndarray:
     return lens.astype(np.int32)
 
 
-def _normal(rng: np.random.Generator, shape, std: float, dtype: str, chunk_rows: int = 4096) -> np.ndarray:
+_CHUNK_ROWS = 1024
+_POOL = ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1))
+
+
+def _normal(seed: int, name: str, layer: int, shape, std: float, dtype: str) -> np.ndarray:
+    """N(0, std) values rounded to `dtype`.  Rows are drawn in fixed chunks of 1024, each
+    chunk from its own stream (seed, name, layer, chunk), so chunks can be filled in
+    parallel and the result does not depend on the number of threads."""
     out = np.empty(shape, dtype=np.float32)
     flat = out.reshape(shape[0], -1) if len(shape) > 1 else out.reshape(1, -1)
-    for r0 in range(0, flat.shape[0], chunk_rows):
-        blk = rng.standard_normal(flat[r0:r0 + chunk_rows].shape, dtype=np.float32)
+
+    def fill(c):
+        r0 = c * _CHUNK_ROWS
+        dst = flat[r0:r0 + _CHUNK_ROWS]
+        blk = _stream(seed, name, layer, c).standard_normal(dst.shape, dtype=np.float32)
         if std != 1.0:
             blk *= np.float32(std)
-        flat[r0:r0 + chunk_rows] = round_to_dtype(blk, dtype)
+        dst[...] = round_to_dtype(blk, dtype)
+
+    n_chunks = (flat.shape[0] + _CHUNK_ROWS - 1) // _CHUNK_ROWS
+    if n_chunks <= 1:
+        fill(0)
+    else:
+        list(_POOL.map(fill, range(n_chunks)))
     return out
 
 
@@ -120,8 +138,14 @@ def sample_x(w: Workload, seed: int = 0, seqs=None) -> np.ndarray:
     each sequence has its own stream so a subset costs only its share."""
     idx = list(range(w.batch)) if seqs is None else [int(b) for b in seqs]
     out = np.empty((len(idx), w.max_len, w.hidden), dtype=np.float32)
-    for o, b in enumerate(idx):
-        out[o] = _normal(_stream(seed, "x", b), (w.max_len, w.hidden), 1.0, w.dtype)
+    def one(ob):
+        out[ob[0]] = _normal(seed, "x", ob[1], (w.max_len, w.hidden), 1.0, w.dtype)
+
+    if w.max_len <= _CHUNK_ROWS:      # one chunk per sequence: spread the sequences over threads
+        list(_POOL.map(one, enumerate(idx)))
+    else:                             # several chunks per sequence: _normal spreads those
+        for ob in enumerate(idx):
+            one(ob)
     return out
 
 
@@ -134,7 +158,7 @@ def sample_layer(w: Workload, layer: int, seed: int = 0) -> dict:
     shift 0; weights and biases ~ N(0, 0.02).  A row-split shard (Sec. 4.1.3) has
     no out-proj / FC2 bias: that bias is added after the cross-GPU sum."""
     H, A, F = w.hidden, w.attn_width, w.ffn
-    g = lambda name, shape: _normal(_stream(seed, name, layer), shape, WEIGHT_STD, w.dtype)
+    g = lambda name, shape: _normal(seed, name, layer, shape, WEIGHT_STD, w.dtype)
     p = {
         "ln1_g": np.ones(H, np.float32), "ln1_b": np.zeros(H, np.float32),
         "w_qkv": g("w_qkv", (3 * A, H)), "b_qkv": g("b_qkv", (3 * A,)),

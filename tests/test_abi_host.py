@@ -1,0 +1,129 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+function include/energon.h declares, and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2209_02341_amd import binding as E
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # non-NULL, 256-byte aligned; never dereferenced because validation fails first
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "energon.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(energon_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"energon_pack", "energon_unpack", "energon_layer_forward"} <= set(names)
+    lib = E.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror():
+    assert E.strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert E.strerror(code) not in ("ok", "unknown status")
+    assert E.strerror(-99) == "unknown status"
+
+
+def cfg(**kw):
+    base = dict(hidden=1024, n_heads=16, head_dim=64, ffn=4096, ln_eps=1e-5, dtype=E.BF16)
+    base.update(kw)
+    return E.LayerConfig(**base)
+
+
+def test_workspace_sizes():
+    c = cfg()
+    assert E.energon_workspace_bytes(c, 0) > 0
+    T = 577
+    need = sum(T * n * 2 for n in (1024, 3072, 1024, 1024, 1024, 4096))
+    got = E.energon_workspace_bytes(c, T)
+    assert need <= got <= need + 6 * 256
+    off = E.energon_workspace_layout(c, T)
+    assert off[0] == 0 and all(o % 256 == 0 for o in off) and off == sorted(off)
+    assert off[E.WS_QKV] >= T * 1024 * 2
+    assert E.energon_workspace_bytes(cfg(head_dim=96, n_heads=8), 10) == 0
+    assert E.energon_workspace_bytes(cfg(hidden=1000), 10) == 0
+    assert E.energon_workspace_bytes(c, -1) == 0
+    assert E.energon_workspace_bytes(cfg(dtype=E.F32, hidden=260, n_heads=1, ffn=8), 3) > 0
+
+
+def pack_status(lengths, B=2, S=4, H=64, dt=E.BF16, x=FAKE, xp=FAKE, cap=8, cu=FAKE, idx=FAKE):
+    lens = np.asarray(lengths, dtype=np.int32)
+    tot = C.c_int64(-5)
+    st = E.lib().energon_pack(x, lens.ctypes.data, B, S, H, dt, xp, cap, cu, idx, C.byref(tot), None)
+    assert tot.value == -5      # never written on failure
+    return st
+
+
+def test_pack_rejects_bad_arguments_before_any_launch():
+    assert pack_status([1, 2], x=None) == -1
+    assert pack_status([1, 2], cu=None) == -1
+    assert pack_status([1, 2], dt=7) == -6
+    assert pack_status([1, 2], H=60) == -2
+    assert pack_status([1, 2], B=0) == -2
+    assert pack_status([1, 5]) == -3
+    assert pack_status([-1, 2]) == -3
+    assert pack_status([4, 4], cap=7) == -4
+    assert pack_status([1, 2], x=FAKE + 8) == -5
+    assert pack_status([1, 2], B=2, S=1 << 30) == -2
+
+
+def test_unpack_rejects_bad_arguments():
+    f = E.lib().energon_unpack
+    assert f(None, FAKE, 3, 2, 4, 64, E.BF16, FAKE, None) == -1
+    assert f(FAKE, FAKE, 9, 2, 4, 64, E.BF16, FAKE, None) == -2
+    assert f(FAKE, FAKE, 3, 2, 4, 63, E.F32, FAKE, None) == -2
+    assert f(FAKE, FAKE, 3, 2, 4, 64, 5, FAKE, None) == -6
+    assert f(FAKE, FAKE + 4, 3, 2, 4, 64, E.BF16, FAKE + 2, None) == -5
+
+
+def layer_status(c=None, w=None, lengths=(3, 2), T=5, max_len=4, x=FAKE, y=FAKE, cu=FAKE, ws=FAKE, ws_bytes=1 << 30):
+    c = c or cfg()
+    if w is None:
+        w = E.LayerWeights(*([FAKE] * 12))
+    lens = np.asarray(lengths, dtype=np.int32)
+    return E.lib().energon_layer_forward(C.byref(c), C.byref(w), x, y, T, cu, lens.ctypes.data, len(lens), max_len,
+                                         ws, ws_bytes, None)
+
+
+def test_layer_forward_rejects_bad_arguments():
+    assert layer_status(x=None) == -1
+    w = E.LayerWeights(*([FAKE] * 12)); w.w_fc1 = None
+    assert layer_status(w=w) == -1
+    assert layer_status(c=cfg(head_dim=80, n_heads=16)) == -6
+    assert layer_status(c=cfg(dtype=3)) == -6
+    assert layer_status(c=cfg(ffn=4100)) == -2
+    assert layer_status(c=cfg(hidden=0)) == -2
+    assert layer_status(T=6) == -3                 # lengths do not sum to T
+    assert layer_status(lengths=(5, 0)) == -3      # longer than max_len
+    assert layer_status(ws_bytes=1024) == -4
+    assert layer_status(ws=FAKE + 16) == -5
+    assert layer_status(y=FAKE + 2) == -5
+    st = E.lib().energon_layer_forward_profiled
+    c, w = cfg(), E.LayerWeights(*([FAKE] * 12))
+    lens = np.asarray([3, 2], dtype=np.int32)
+    assert st(C.byref(c), C.byref(w), FAKE, FAKE, 5, FAKE, lens.ctypes.data, 2, 4, FAKE, 1 << 30, None, None) == -1
+
+
+def test_stage_entry_points_reject_bad_arguments():
+    l = E.lib()
+    assert l.energon_layernorm(FAKE, FAKE, None, FAKE, 4, 64, 1e-5, E.BF16, None) == -1
+    assert l.energon_layernorm(FAKE, FAKE, FAKE, FAKE, 4, 62, 1e-5, E.BF16, None) == -2
+    assert l.energon_layernorm(FAKE, FAKE, FAKE, FAKE, 4, 1 << 20, 1e-5, E.BF16, None) == -6
+    assert l.energon_linear(FAKE, FAKE, None, None, FAKE, 4, 64, 64, E.EPI_BIAS_RESIDUAL, E.BF16, None) == -1
+    assert l.energon_linear(FAKE, FAKE, None, None, FAKE, 4, 64, 96, E.EPI_BIAS, E.BF16, None) == -2
+    assert l.energon_linear(FAKE, FAKE, None, None, FAKE, 4, 64, 64, 9, E.BF16, None) == -6
+    assert l.energon_linear(FAKE, FAKE, FAKE + 2, None, FAKE, 4, 64, 64, E.EPI_BIAS, E.BF16, None) == -5
+    assert l.energon_attention(FAKE, FAKE, FAKE, 5, 2, 4, 2, 32, E.BF16, None) == -6
+    assert l.energon_attention(FAKE, None, FAKE, 5, 2, 4, 2, 64, E.BF16, None) == -1
+    assert l.energon_attention(FAKE, FAKE, FAKE, 5, 0, 4, 2, 64, E.BF16, None) == -2
+    assert l.energon_attention(FAKE, FAKE, FAKE, 0, 2, 4, 2, 64, E.BF16, None) == 0   # T = 0: nothing to do

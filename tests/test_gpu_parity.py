@@ -1,0 +1,258 @@
+"""GPU parity: every stage and the whole pack -> layers -> unpack path, called through the
+C ABI, against the CPU fp64 oracle on the same seeded inputs.
+
+Bars: integer / byte work (compaction indices, gathered and scattered rows, zero fill) is
+bit-exact.  Floating point: max|gpu - oracle| / max|oracle| <= 1e-2 per tensor for bf16
+storage (fp32 accumulation; one bf16 rounding per stage boundary, 2^-9 relative each) and
+<= 1e-4 for fp32 storage; plus elementwise |gpu - oracle| <= tol*|oracle| + tol*rms(oracle).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import energon_oracle as orc
+from paper_2209_02341_amd import binding as E
+from paper_2209_02341_amd import harness as hz
+from paper_2209_02341_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {wl.BF16: 1e-2, wl.F32: 1e-4}
+
+
+def assert_close(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str, tol=None):
+    tol = tol or TOL[dtype]
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    if ref.size == 0:
+        return
+    assert np.all(np.isfinite(gpu)), what
+    err = np.abs(gpu - ref)
+    scale = np.abs(ref).max()
+    rms = np.sqrt(np.mean(ref ** 2))
+    assert err.max() <= tol * scale, f"{what}: max err {err.max():.3e} vs scale {scale:.3e}"
+    bad = err > tol * np.abs(ref) + tol * rms
+    assert not bad.any(), f"{what}: {bad.sum()} elements outside tol, worst {err[bad].max():.3e}"
+
+
+def tdtype(dtype):
+    return torch.bfloat16 if dtype == wl.BF16 else torch.float32
+
+
+# ------------------------------------------------------------------ pack / unpack (bit-exact)
+PACK_CASES = [
+    # B, S, H, lengths (None = random incl. zeros), dtype
+    (4, 32, 256, None, wl.F32),
+    (8, 128, 1024, None, wl.BF16),
+    (5, 7, 8, [7, 0, 3, 0, 1], wl.BF16),
+    (3, 5, 4, [0, 0, 0], wl.F32),
+    (2, 9, 72, [9, 9], wl.BF16),
+    (130, 3, 64, None, wl.BF16),        # more sequences than one wavefront scans at once
+    (32, 512, 5120, None, wl.BF16),     # the 13B-shape batch
+]
+
+
+@pytest.mark.parametrize("B,S,H,lengths,dtype", PACK_CASES)
+def test_pack_unpack_bit_exact(B, S, H, lengths, dtype):
+    rng = np.random.default_rng(B * 1000 + S)
+    lens = np.asarray(lengths if lengths is not None else rng.integers(0, S + 1, size=B), dtype=np.int32)
+    x = torch.randn((B, S, H), generator=torch.Generator().manual_seed(1), dtype=torch.float32)
+    x = x.to(tdtype(dtype)).cuda()
+    T_ref = int(lens.sum())
+    cap = T_ref + 3
+    xp = torch.full((cap, H), 7.0, dtype=x.dtype, device="cuda")
+    cu = torch.full((B + 1,), -1, dtype=torch.int32, device="cuda")
+    idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    T = E.energon_pack(x, lens, xp, cu, idx)
+    cu_ref, idx_ref = orc.pack_indices(lens, S)
+    assert T == T_ref
+    assert np.array_equal(cu.cpu().numpy(), cu_ref)
+    assert np.array_equal(idx.cpu().numpy()[:T], idx_ref)
+    assert np.all(idx.cpu().numpy()[T:] == -1)
+    bits = lambda t: t.contiguous().view(torch.int16 if dtype == wl.BF16 else torch.int32).cpu().numpy()
+    ref_rows = bits(x).reshape(B * S, H)[idx_ref]
+    assert np.array_equal(bits(xp)[:T], ref_rows)
+    assert np.array_equal(bits(xp)[T:], bits(torch.full((3, H), 7.0, dtype=x.dtype)))   # untouched
+    y = torch.full((B, S, H), 5.0, dtype=x.dtype, device="cuda")
+    E.energon_unpack(xp, cu, T, y)
+    yb, xb = bits(y), bits(x)
+    for b in range(B):
+        assert np.array_equal(yb[b, :lens[b]], xb[b, :lens[b]])
+        assert np.all(yb[b, lens[b]:] == 0)
+
+
+# ------------------------------------------------------------------ stages
+@pytest.mark.parametrize("T,H,dtype", [(37, 256, wl.F32), (300, 1024, wl.BF16), (64, 5120, wl.BF16),
+                                        (5, 8, wl.BF16), (9, 12288, wl.BF16), (3, 16384, wl.F32)])
+def test_layernorm(T, H, dtype):
+    rng = np.random.default_rng(T + H)
+    x = wl.round_to_dtype(rng.standard_normal((T, H)) * 2 + 0.5, dtype)
+    g = wl.round_to_dtype(1 + 0.3 * rng.standard_normal(H), dtype)
+    b = wl.round_to_dtype(0.2 * rng.standard_normal(H), dtype)
+    xd, gd, bd = (hz.to_device(a, dtype) for a in (x, g, b))
+    yd = torch.empty_like(xd)
+    E.energon_layernorm(xd, gd, bd, yd, 1e-5)
+    ref = orc.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5)
+    assert_close(hz.to_host(yd), ref, dtype, "layernorm")
+
+
+LINEAR_CASES = [
+    # M, N, K, dtype : several tiles in M and N, ragged tails in both, several K slabs
+    (300, 264, 192, wl.BF16), (1, 8, 64, wl.BF16), (515, 1024, 1024, wl.BF16), (257, 520, 128, wl.BF16),
+    (70, 132, 36, wl.F32), (1, 4, 4, wl.F32), (130, 256, 256, wl.F32),
+]
+
+
+@pytest.mark.parametrize("M,N,K,dtype", LINEAR_CASES)
+@pytest.mark.parametrize("epi", [E.EPI_BIAS, E.EPI_BIAS_GELU, E.EPI_BIAS_RESIDUAL])
+def test_linear(M, N, K, dtype, epi):
+    rng = np.random.default_rng(M * 7 + N + K + epi)
+    x = wl.round_to_dtype(rng.standard_normal((M, K)), dtype)
+    w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
+    b = wl.round_to_dtype(rng.standard_normal(N) * 0.5, dtype)
+    r = wl.round_to_dtype(rng.standard_normal((M, N)), dtype)
+    for bias in (b, None):
+        xd, wd, bd, rd = (hz.to_device(a, dtype) for a in (x, w, bias, r))
+        yd = torch.full((M + 1, N), 3.0, dtype=xd.dtype, device="cuda")
+        E.energon_linear(xd, wd, bd, rd if epi == E.EPI_BIAS_RESIDUAL else None, yd, epi)
+        ref = orc.linear(x.astype(np.float64), w.astype(np.float64), None if bias is None else bias.astype(np.float64))
+        if epi == E.EPI_BIAS_GELU:
+            ref = orc.gelu(ref)
+        if epi == E.EPI_BIAS_RESIDUAL:
+            ref = ref + r
+        out = hz.to_host(yd)
+        assert_close(out[:M], ref, dtype, f"linear epi={epi}")
+        assert np.all(out[M] == 3.0), "row past M was written"
+
+
+def test_linear_residual_in_place():
+    dtype, M, N, K = wl.BF16, 130, 256, 128
+    rng = np.random.default_rng(5)
+    x = wl.round_to_dtype(rng.standard_normal((M, K)), dtype)
+    w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
+    r = wl.round_to_dtype(rng.standard_normal((M, N)), dtype)
+    xd, wd, rd = (hz.to_device(a, dtype) for a in (x, w, r))
+    E.energon_linear(xd, wd, None, rd, rd, E.EPI_BIAS_RESIDUAL)
+    assert_close(hz.to_host(rd), x.astype(np.float64) @ w.astype(np.float64).T + r, dtype, "in-place residual")
+
+
+ATTN_CASES = [
+    ([5, 0, 1, 64, 65, 130], 2, 64, wl.BF16), ([128, 16, 77], 3, 128, wl.BF16), ([300], 1, 128, wl.BF16),
+    ([257, 3], 2, 64, wl.BF16), ([9, 32, 1], 4, 64, wl.F32), ([70], 1, 128, wl.F32),
+]
+
+
+@pytest.mark.parametrize("lengths,nh,d,dtype", ATTN_CASES)
+def test_attention(lengths, nh, d, dtype):
+    rng = np.random.default_rng(sum(lengths) + nh + d)
+    lens = np.asarray(lengths, dtype=np.int32)
+    T, A, B = int(lens.sum()), nh * d, len(lens)
+    qkv = wl.round_to_dtype(rng.standard_normal((T, 3 * A)), dtype)
+    cu_ref, _ = orc.pack_indices(lens, int(lens.max()))
+    qd = hz.to_device(qkv, dtype)
+    od = torch.full((T + 1, A), 3.0, dtype=qd.dtype, device="cuda")
+    cud = torch.from_numpy(cu_ref).cuda()
+    E.energon_attention(qd, od[:T], cud, B, int(lens.max()), nh, d)
+    out = hz.to_host(od)
+    assert np.all(out[T] == 3.0)
+    q64 = qkv.astype(np.float64)
+    for b in range(B):
+        s0, s1 = cu_ref[b], cu_ref[b + 1]
+        if s1 == s0:
+            continue
+        blk = q64[s0:s1]
+        ref = orc.masked_causal_attention(blk[:, :A], blk[:, A:2 * A], blk[:, 2 * A:], int(lens[b]), nh, d)
+        assert_close(out[s0:s1], ref, dtype, f"attention seq {b}")
+
+
+# ------------------------------------------------------------------ whole path
+def run_gpu(w: wl.Workload, x: np.ndarray, lens: np.ndarray, layers: list, pad_fill=None):
+    cfg = hz.layer_config(w.hidden, w.n_heads, w.head_dim, w.ffn, w.dtype, w.ln_eps)
+    B, S, _ = x.shape
+    xin = x.copy()
+    if pad_fill is not None:
+        for b in range(B):
+            xin[b, lens[b]:] = pad_fill
+    run = hz.PackedRun(cfg, B, S, int(lens.sum()))
+    dev_layers = [hz.DeviceLayer(p, w.dtype) for p in layers]
+    y = run.forward(hz.to_device(xin, w.dtype), lens, dev_layers)
+    torch.cuda.synchronize()
+    return run, y
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
+def test_layer_forward_matches_oracle_with_intermediates(name):
+    w = wl.WORKLOADS[name]
+    lens, x, layers = wl.sample_lengths(w), wl.sample_x(w), [wl.sample_layer(w, 0)]
+    run, y = run_gpu(w, x, lens, layers)
+    st = {}
+    ref = orc.stack_forward(x, lens, layers, w.n_heads, w.head_dim, w.ln_eps, stages=st)
+    out = hz.to_host(y)
+    A = w.attn_width
+    for key, which, cols in (("u", E.WS_U, w.hidden), ("qkv", E.WS_QKV, 3 * A), ("attn", E.WS_ATTN, A),
+                             ("y1", E.WS_Y1, w.hidden), ("w", E.WS_W, w.hidden), ("m", E.WS_M, w.ffn)):
+        got = hz.to_host(run.stage(which, cols))
+        assert_close(got, orc.pack(st[key], lens), w.dtype, f"{name} stage {key}")
+    for b in range(w.batch):
+        assert np.all(out[b, lens[b]:] == 0)
+    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, f"{name} output")
+
+
+def test_padding_content_never_read_bitwise():
+    w = wl.WORKLOADS["small_bf16"]
+    lens, x, layers = wl.sample_lengths(w), wl.sample_x(w), [wl.sample_layer(w, 0)]
+    _, y0 = run_gpu(w, x, lens, layers)
+    y0 = y0.clone()
+    for fill in (0.0, 1e4, float("nan")):
+        _, y1 = run_gpu(w, x, lens, layers, pad_fill=fill)
+        assert torch.equal(y0.view(torch.int16), y1.view(torch.int16))
+
+
+def test_padded_path_agrees_with_packed_path():
+    """The no-elimination baseline: same kernels, every position treated as valid."""
+    w = wl.WORKLOADS["small_bf16"]
+    lens, x, layers = wl.sample_lengths(w), wl.sample_x(w), [wl.sample_layer(w, 0)]
+    _, y_packed = run_gpu(w, x, lens, layers)
+    full = np.full(w.batch, w.max_len, dtype=np.int32)
+    _, y_padded = run_gpu(w, x, full, layers)
+    a, b = hz.to_host(y_packed), hz.to_host(y_padded)
+    assert_close(orc.pack(b, lens), orc.pack(a, lens), w.dtype, "padded vs packed", tol=4e-3)
+
+
+def test_two_layer_stack_medium_shape():
+    w = wl.Workload("medium", wl.BF16, 2, 512, 4, 128, 1024, 5, 96, "uniform", 0, 96)
+    lens = np.array([96, 0, 33, 1, 70], dtype=np.int32)
+    x, layers = wl.sample_x(w), [wl.sample_layer(w, 0), wl.sample_layer(w, 1)]
+    _, y = run_gpu(w, x, lens, layers)
+    ref = orc.stack_forward(x, lens, layers, w.n_heads, w.head_dim, w.ln_eps)
+    out = hz.to_host(y)
+    assert np.all(out[1] == 0)
+    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, "two-layer stack")
+
+
+def test_empty_batch_is_legal():
+    w = wl.Workload("empty", wl.BF16, 1, 128, 2, 64, 256, 3, 8, "uniform", 0, 0)
+    lens = np.zeros(3, dtype=np.int32)
+    _, y = run_gpu(w, wl.sample_x(w), lens, [wl.sample_layer(w, 0)])
+    assert torch.count_nonzero(y.float()).item() == 0
+
+
+def test_full_size_13b_shape_sampled_sequences():
+    """The benchmark's workload at full size (T ~ 8.7k rows, 4 layers of hidden 5120): the
+    oracle follows the two shortest sequences through the whole stack; sequences are
+    independent, so their rows must match the full-batch GPU run."""
+    w = wl.WORKLOADS["gpt13b_bf16"]
+    lens = wl.sample_lengths(w)
+    x = wl.sample_x(w)
+    layers = [wl.sample_layer(w, l) for l in range(w.layers)]
+    _, y = run_gpu(w, x, lens, layers)
+    picks = np.argsort(lens)[:2]
+    out = hz.to_host(y[torch.from_numpy(picks).cuda()])
+    sub_len = lens[picks]
+    S_sub = int(sub_len.max())
+    ref = orc.stack_forward(x[picks][:, :S_sub], sub_len, layers, w.n_heads, w.head_dim, w.ln_eps)
+    assert_close(orc.pack(out[:, :S_sub], sub_len), orc.pack(ref, sub_len), w.dtype, "13B-shape sampled sequences")
+    assert np.all(out[0, sub_len[0]:] == 0)
+    # pad rows of the whole output are zero, valid rows are not
+    yz = y.float().abs().sum(dim=2).cpu().numpy()
+    for b in range(w.batch):
+        assert np.all(yz[b, lens[b]:] == 0) and np.all(yz[b, :lens[b]] > 0)
