@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed (padding-free) transformer-layer forward on one MI355X.
+
+One step = the whole hot path on one synthetic batch: pack (length scan + gather), L layer
+forwards on the packed rows, unpack (scatter + zero fill).  Inputs are resident in HBM before
+the timed region.  Prints ONE JSON line:
+  value      effective (non-pad) tokens/s per layer forward = T * L / step time
+  roofline   the bf16 MFMA GEMM kernel (the dominant kernel): algorithmic flops of the four
+             GEMMs of a layer / their launch durations, measured with HIP events recorded on
+             the launch stream between the stages (energon_layer_forward_profiled)
+  padded     the same library run with every position treated as valid (no elimination)
+  cpu_baseline  the CPU oracle timed on a bounded sample of whole sequences, one layer
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt13b_bf16")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-padded", action="store_true")
+    ap.add_argument("--cpu-sample-seqs", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2209_02341_amd import binding as E
+    from paper_2209_02341_amd import harness as hz
+    from paper_2209_02341_amd import workloads as wl
+
+    E.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    w = wl.WORKLOADS[args.workload]
+    L, H, A, F, B, S = w.layers, w.hidden, w.attn_width, w.ffn, w.batch, w.max_len
+    esz = 2 if w.dtype == wl.BF16 else 4
+    lens = wl.sample_lengths(w, args.seed)
+    T = int(lens.sum())
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    log(f"[bench] workload {w.name}: B={B} S={S} H={H} heads={w.n_heads}x{w.head_dim} F={F} L={L} "
+        f"T={T} ({T / (B * S):.1%} valid)")
+
+    x_host = wl.sample_x(w, args.seed)
+    x_dev = hz.to_device(x_host, w.dtype)
+    host_layers = []
+    dev_layers = []
+    for l in range(L):
+        p = wl.sample_layer(w, l, args.seed)
+        dev_layers.append(hz.DeviceLayer(p, w.dtype))
+        host_layers.append(p if l == 0 else None)   # the CPU sample uses layer 0 only
+    log("[bench] inputs resident on the GPU")
+    cfg = hz.layer_config(H, w.n_heads, w.head_dim, F, w.dtype, w.ln_eps)
+
+    def time_steps(run, lengths, steps, warmup):
+        for _ in range(warmup):
+            run.forward(x_dev, lengths, dev_layers)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run.forward(x_dev, lengths, dev_layers)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    run = hz.PackedRun(cfg, B, S, T)
+    ms_step = time_steps(run, lens, args.steps, args.warmup)
+    ms_layer = ms_step / L
+    value = T / (ms_layer * 1e-3)
+    gemm_flops_layer = T * (8.0 * H * A + 4.0 * H * F)
+    attn_flops_layer = 2.0 * A * float(np.sum(lens.astype(np.float64) * (lens + 1)))
+    flops_layer = gemm_flops_layer + attn_flops_layer
+    tflops = flops_layer / (ms_layer * 1e-3) / 1e12
+    log(f"[bench] packed: {ms_step:.3f} ms/step, {value:,.0f} tokens/s/layer, {tflops:.1f} TFLOP/s")
+
+    # ---- per-stage durations (HIP events on the launch stream), same kernels, same buffers ----
+    stage_ms = {k: 0.0 for k in E.STAGE_NAMES}
+    n_prof = max(1, min(args.steps, 10))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    pack_ms = unpack_ms = 0.0
+    for _ in range(n_prof):
+        ev[0].record()
+        E.energon_pack(x_dev, lens, run.x_packed, run.cu, run.idx)
+        ev[1].record()
+        src, dst = run.x_packed, run.y_packed
+        for layer in dev_layers:
+            ms = E.energon_layer_forward_profiled(cfg, layer.struct, src, dst, T, run.cu, lens, S, run.workspace)
+            for k, v in ms.items():
+                stage_ms[k] += v
+            src, dst = dst, src
+        ev[2].record()
+        E.energon_unpack(src, run.cu, T, run.y_padded)
+        ev[3].record()
+        torch.cuda.synchronize()
+        pack_ms += ev[0].elapsed_time(ev[1])
+        unpack_ms += ev[2].elapsed_time(ev[3])
+    n_layer_calls = n_prof * L
+    stage_ms = {k: v / n_layer_calls for k, v in stage_ms.items()}
+    pack_ms /= n_prof
+    unpack_ms /= n_prof
+    gemm_ms = sum(stage_ms[k] for k in ("qkv", "out", "fc1", "fc2"))
+    gemm_tflops = gemm_flops_layer / (gemm_ms * 1e-3) / 1e12
+    gbs = lambda nbytes, ms: nbytes / (ms * 1e-3) / 1e9 if ms > 0 else None
+    hbm = {
+        "pack_GBs": gbs(2.0 * T * H * esz, pack_ms),
+        "unpack_GBs": gbs((T + B * S) * H * esz, unpack_ms),
+        "layernorm_GBs": gbs(2.0 * T * H * esz * 2, stage_ms["ln1"] + stage_ms["ln2"]),
+        "peak_GBs": PEAK_HBM_GBS,
+    }
+    stage_tflops = {
+        "qkv": 2.0 * T * 3 * A * H / (stage_ms["qkv"] * 1e9), "out": 2.0 * T * H * A / (stage_ms["out"] * 1e9),
+        "fc1": 2.0 * T * F * H / (stage_ms["fc1"] * 1e9), "fc2": 2.0 * T * H * F / (stage_ms["fc2"] * 1e9),
+        "attn": attn_flops_layer / (stage_ms["attn"] * 1e9),
+    }
+    log(f"[bench] stages (ms/layer): " + ", ".join(f"{k}={v:.3f}" for k, v in stage_ms.items()) +
+        f"; pack={pack_ms:.3f} unpack={unpack_ms:.3f}; GEMMs {gemm_tflops:.1f} TFLOP/s")
+
+    # ---- padded (no-elimination) path: same library, every position valid ----
+    padded = None
+    if not args.no_padded:
+        full = np.full(B, S, dtype=np.int32)
+        del run
+        torch.cuda.empty_cache()
+        run_p = hz.PackedRun(cfg, B, S, B * S)
+        ms_pad = time_steps(run_p, full, max(2, args.steps // 2), min(args.warmup, 2))
+        padded = {"ms_per_step": ms_pad, "value": T / (ms_pad / L * 1e-3), "rows": B * S,
+                  "speedup_packed_over_padded": ms_pad / ms_step, "rows_ratio": B * S / T}
+        log(f"[bench] padded: {ms_pad:.3f} ms/step -> packed is {ms_pad / ms_step:.2f}x faster "
+            f"(row ratio {B * S / T:.2f})")
+        del run_p
+        torch.cuda.empty_cache()
+
+    # ---- CPU oracle on a bounded sample: whole sequences near the median length, one layer ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import energon_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        order = np.argsort(np.abs(lens - np.median(lens)))
+        picks = np.sort(order[: args.cpu_sample_seqs])
+        sub_len = lens[picks]
+        s_sub = int(sub_len.max())
+        t0 = time.perf_counter()
+        orc.stack_forward(x_host[picks][:, :s_sub], sub_len, [host_layers[0]], w.n_heads, w.head_dim, w.ln_eps)
+        dt = time.perf_counter() - t0
+        cpu = {"value": float(sub_len.sum()) / dt, "unit": "tokens/s per layer forward", "cores": int(threads),
+               "kind": "oracle", "seconds": dt,
+               "sample": f"{len(picks)} whole sequences nearest the median length "
+                         f"({int(sub_len.sum())} valid tokens, padded to {s_sub}), one layer at full layer shape, "
+                         f"NumPy fp64"}
+        log(f"[bench] cpu oracle sample: {dt:.1f} s -> {cpu['value']:.1f} tokens/s/layer on {threads} threads")
+
+    out = {
+        "metric": "effective (non-pad) tokens/s per layer forward",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers": L, "hidden": H, "heads": w.n_heads, "head_dim": w.head_dim,
+                   "ffn": F, "batch": B, "max_len": S, "valid_tokens": T, "valid_fraction": T / (B * S),
+                   "step": "pack + L x layer_forward + unpack"},
+        "ms_per_layer": ms_layer, "tflops": tflops, "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": None,
+                     "launches_per_layer": 4, "avg_launch_ms": gemm_ms / 4,
+                     "flops_per_launch": gemm_flops_layer / 4},
+        "stage_ms_per_layer": stage_ms, "stage_tflops": stage_tflops,
+        "pack_ms": pack_ms, "unpack_ms": unpack_ms, "hbm": hbm,
+        "padded": padded, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

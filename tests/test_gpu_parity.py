@@ -4,7 +4,8 @@ C ABI, against the CPU fp64 oracle on the same seeded inputs.
 Bars: integer / byte work (compaction indices, gathered and scattered rows, zero fill) is
 bit-exact.  Floating point: max|gpu - oracle| / max|oracle| <= 1e-2 per tensor for bf16
 storage (fp32 accumulation; one bf16 rounding per stage boundary, 2^-9 relative each) and
-<= 1e-4 for fp32 storage; plus elementwise |gpu - oracle| <= tol*|oracle| + tol*rms(oracle).
+<= 1e-4 for fp32 storage; plus, so that one wrong row cannot hide behind larger rows,
+elementwise |gpu - oracle| <= tol*|oracle| + tol*max|oracle row|.
 """
 import numpy as np
 import pytest
@@ -28,9 +29,9 @@ def assert_close(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str, tol=No
     assert np.all(np.isfinite(gpu)), what
     err = np.abs(gpu - ref)
     scale = np.abs(ref).max()
-    rms = np.sqrt(np.mean(ref ** 2))
     assert err.max() <= tol * scale, f"{what}: max err {err.max():.3e} vs scale {scale:.3e}"
-    bad = err > tol * np.abs(ref) + tol * rms
+    row_scale = np.abs(ref).reshape(-1, ref.shape[-1]).max(axis=1).reshape(ref.shape[:-1] + (1,))
+    bad = err > tol * np.abs(ref) + tol * row_scale
     assert not bad.any(), f"{what}: {bad.sum()} elements outside tol, worst {err[bad].max():.3e}"
 
 
@@ -236,6 +237,7 @@ def test_empty_batch_is_legal():
     assert torch.count_nonzero(y.float()).item() == 0
 
 
+@pytest.mark.timeout(600)
 def test_full_size_13b_shape_sampled_sequences():
     """The benchmark's workload at full size (T ~ 8.7k rows, 4 layers of hidden 5120): the
     oracle follows the two shortest sequences through the whole stack; sequences are
