@@ -105,13 +105,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
   for (int kt = 0; kt < KT; ++kt) {
     const uint4* cur = smem + (kt & 1) * kStage;
     uint4* nxt = smem + ((kt + 1) & 1) * kStage;
-    const bool more = kt + 1 < KT;
-    if (more) {
+    // the slab after the last one does not exist: fetch the last slab again (never read)
+    const int knext = (kt + 1 < KT ? kt + 1 : kt) * kChunks;
 #pragma unroll
-      for (int i = 0; i < CA; ++i) ra[i] = ga[i][(kt + 1) * kChunks];
+    for (int i = 0; i < CA; ++i) ra[i] = ga[i][knext];
 #pragma unroll
-      for (int i = 0; i < CB; ++i) rb[i] = gb[i][(kt + 1) * kChunks];
-    }
+    for (int i = 0; i < CB; ++i) rb[i] = gb[i][knext];
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 af[TM], bfr[TN];
@@ -126,12 +125,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const bf16_t* __
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
 #pragma unroll
-      for (int i = 0; i < CA; ++i) nxt[sa[i]] = ra[i];
+    for (int i = 0; i < CA; ++i) nxt[sa[i]] = ra[i];
 #pragma unroll
-      for (int i = 0; i < CB; ++i) nxt[sb[i]] = rb[i];
-    }
+    for (int i = 0; i < CB; ++i) nxt[sb[i]] = rb[i];
     __syncthreads();
   }
 
