@@ -138,7 +138,8 @@ def test_linear_residual_in_place():
 
 ATTN_CASES = [
     ([5, 0, 1, 64, 65, 130], 2, 64, wl.BF16), ([128, 16, 77], 3, 128, wl.BF16), ([300], 1, 128, wl.BF16),
-    ([257, 3], 2, 64, wl.BF16), ([9, 32, 1], 4, 64, wl.F32), ([70], 1, 128, wl.F32),
+    ([257, 3], 2, 64, wl.BF16), ([513, 200, 128, 127], 2, 128, wl.BF16), ([384, 129], 1, 64, wl.BF16),
+    ([9, 32, 1], 4, 64, wl.F32), ([70], 1, 128, wl.F32),
 ]
 
 
