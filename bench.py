@@ -24,6 +24,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# Bytes per GEMM launch at the L2 -> fabric boundary (mean of the four GEMMs of a layer), from the
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_gpt13b_bf16_hbm_traffic.md.
+GEMM_TRAFFIC_BYTES = {"gpt13b_bf16": 2679e6}
 
 
 def main():
@@ -35,7 +38,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
-    ap.add_argument("--cpu-sample-seqs", type=int, default=2)
+    ap.add_argument("--cpu-sample-seqs", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -83,6 +86,9 @@ def main():
     ms_layer = ms_step / L
     value = T / (ms_layer * 1e-3)
     gemm_flops_layer = T * (8.0 * H * A + 4.0 * H * F)
+    # x and W read once, y written once, residual read once (out-proj, FC2)
+    gemm_bytes_layer = esz * (T * (H + 3 * A) + 3.0 * A * H + T * (A + 2 * H) + H * A + T * (H + F) + F * H
+                              + T * (F + 2 * H) + H * F)
     attn_flops_layer = 2.0 * A * float(np.sum(lens.astype(np.float64) * (lens + 1)))
     flops_layer = gemm_flops_layer + attn_flops_layer
     tflops = flops_layer / (ms_layer * 1e-3) / 1e12
@@ -179,7 +185,8 @@ def main():
         "ms_per_layer": ms_layer, "tflops": tflops, "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None,
+                     "traffic": GEMM_TRAFFIC_BYTES.get(w.name),
+                     "algorithmic_bytes_per_launch": gemm_bytes_layer / 4,
                      "launches_per_layer": 4, "avg_launch_ms": gemm_ms / 4,
                      "flops_per_launch": gemm_flops_layer / 4},
         "stage_ms_per_layer": stage_ms, "stage_tflops": stage_tflops,
