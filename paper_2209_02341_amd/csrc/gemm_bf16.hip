@@ -6,20 +6,23 @@
 //  * both operands are contiguous along K, so x rows feed the MFMA A operand and W rows the
 //    B operand with the same 16-byte chunks; v_mfma_f32_32x32x16_bf16, fp32 accumulators;
 //  * a BM x BN output tile per workgroup, K walked in slabs of 64 (128 bytes per row), two
-//    slab buffers in LDS filled straight from global memory (global_load_lds_dwordx4: no
-//    staging registers, no LDS store instructions);
-//  * one such load writes 1 KiB of LDS = 8 rows x 8 chunks in lane order, so the swizzle is
-//    applied on the global side: the lane that lands in slot s of row r fetches chunk
-//    s ^ swz(r).  The 32 rows a wavefront reads for one MFMA operand then fall in distinct
-//    banks (measured: zero bank conflicts);
+//    slab buffers in LDS;
+//  * an LDS row is 8 chunks of 16 bytes; chunk c of row r is stored in slot c ^ swz(r), so the
+//    32 rows a wavefront reads for one MFMA operand fall in distinct banks (measured: zero bank
+//    conflicts).  Slabs are moved in 1 KiB groups = 8 rows x 8 slots in lane order, the lane that
+//    lands in slot s of row r fetching chunk s ^ swz(r): full 128-byte lines on the global side;
 //  * workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2, so the id is
 //    remapped to give every XCD a contiguous run of tiles, ordered in bands of 8 row tiles:
 //    the 32 tiles resident on an XCD form an 8 x 4 block that shares x and W slabs in that L2;
-//  * ragged M (T is arbitrary) and ragged N: loads clamp the row index, stores are predicated;
-//  * epilogue in fp32 on the accumulators: + bias, GeLU(erf) or + residual, one rounding.
-// Two kernels: a hand-scheduled 256x256 tile (4 wavefronts x 128x128, accumulators in AGPRs)
-// for the large layer shapes, and a compiler-scheduled template used with 128x128 tiles when
-// the problem has too few 256x256 tiles to fill the 256 CUs.
+//  * epilogue in fp32: + bias, GeLU(erf) or + residual, one rounding to bf16.
+// Two kernels:
+//  * gemm_bf16_sched_kernel, 256x256 tile, 4 wavefronts x 128x128 with the 256 accumulators in
+//    AGPRs, slab loop hand-scheduled; slab chunks are fetched into registers four slabs ahead and
+//    written to LDS two slabs ahead (a two-slab load window); edge tiles are shifted inwards, so
+//    nothing is clamped or predicated; the epilogue goes through LDS and leaves as 16-byte stores;
+//  * gemm_bf16_tile_kernel, compiler-scheduled, direct-to-LDS loads (global_load_lds_dwordx4),
+//    clamped loads and predicated stores: used with 128x128 tiles for everything the first
+//    kernel does not take (small or ragged-below-one-tile problems, odd slab counts).
 #include "common.h"
 
 namespace energon {
@@ -74,6 +77,64 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const bf
           y[(size_t)m * N + n] = static_cast<bf16_t>(v);
         }
       }
+    }
+  }
+}
+
+// Epilogue of one wavefront's 128x128 tile through LDS, for tiles that lie wholly inside the
+// matrix.  The accumulators go to LDS as fp32 (64 rows at a time, rows padded to 136 floats so
+// the two half-wavefronts of a store hit different banks); each lane then owns 8 consecutive
+// columns of a row: bias, GeLU / residual are applied there in fp32 and the row segment leaves as
+// one 16-byte store, 16 lanes per 256-byte row segment.  One rounding, full-line writes.
+constexpr int kEpiLd = 136;
+constexpr int kEpiWaveFloats = 64 * kEpiLd;
+__device__ __forceinline__ void store_tile_coalesced(const f32x16 (&acc)[4][4], const bf16_t* __restrict__ bias,
+                                                     const bf16_t* res, bf16_t* y, int32_t N, int epi, int64_t mw,
+                                                     int32_t nw, int lane, float* stage) {
+  const int lrow = lane & 31, lhalf = lane >> 5;
+  const int rr = lane >> 4, c8 = (lane & 15) * 8;
+  float bv[8];
+  if (bias != nullptr) {
+    const bf16x8 b8 = *reinterpret_cast<const bf16x8*>(bias + nw + c8);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) bv[q] = static_cast<float>(b8[q]);
+  } else {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) bv[q] = 0.f;
+  }
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    __syncthreads();  // the slab buffers (first pass) / the previous pass's rows are no longer read
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          stage[(ii * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3)) * kEpiLd + j * 32 + lrow] = acc[pass * 2 + ii][j][e];
+    __syncthreads();
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+      const int r = it * 4 + rr;
+      const float4 lo = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8]);
+      const float4 hi = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8 + 4]);
+      float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      const size_t off = (size_t)(mw + pass * 64 + r) * N + nw + c8;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] += bv[q];
+      if (epi == EPI_BIAS_GELU) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = gelu_erf(v[q]);
+      }
+      if (epi == EPI_BIAS_RESIDUAL) {
+        const bf16x8 r8 = *reinterpret_cast<const bf16x8*>(res + off);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] += static_cast<float>(r8[q]);
+      }
+      bf16x8 o;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) o[q] = static_cast<bf16_t>(v[q]);
+      *reinterpret_cast<bf16x8*>(y + off) = o;
     }
   }
 }
@@ -196,15 +257,18 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_tile_kernel(const bf16_
 }
 
 // ---- hand-scheduled 256x256 kernel ----------------------------------------------------------
-// Same tiling and LDS layout, but the slab loop is written as ordered inline-asm
-// statements so that the issue order is exactly the one below (the compiler otherwise re-serialises
-// LDS reads and MFMAs).  One wavefront per SIMD (4 per workgroup), 128x128 per wavefront,
-// accumulators in AGPRs.  Per slab of 64 along K, four steps of 16:
-//   step s   : 16 MFMAs on operand set s, with the 8 LDS reads of step s+1 slotted between them
-//   before step 3: wait for this wavefront's LDS reads and its direct-to-LDS loads of the NEXT
-//              slab, barrier; now the current buffer is free, so the loads of slab kt+2 are issued
-//              into it, and step 3's MFMAs overlap the reads of the next slab's step 0.
-// The barrier thus sits in the shadow of queued MFMAs and the loads have a whole slab to land.
+// The slab loop is written as ordered inline-asm statements so that the issue order is exactly
+// the one below (the compiler otherwise re-serialises LDS reads and MFMAs, and it must not copy
+// or spill a register whose load is still in flight).  One wavefront per SIMD, 128x128 per
+// wavefront.  Per slab of 64 along K, four steps of 16:
+//   step s (0..2): 16 MFMAs on operand set s, the 8 LDS reads of step s+1 slotted after MFMAs 1..8
+//   before step 3: wait for this wavefront's LDS traffic and for the chunks of slab kt+2 (loads
+//              return in order, so "all but the newest 16" suffices), barrier.  The current
+//              buffer is now free.
+//   step 3:    16 MFMAs; after each, one chunk of slab kt+2 goes from its register to the freed
+//              buffer and the register is refilled with the same chunk of slab kt+4; the reads
+//              of the next slab's step 0 (other buffer) are slotted in as above.
+// The barrier thus sits in the shadow of queued MFMAs, and a chunk has two slab times to arrive.
 #define ENERGON_DS_READ(dst, addr, off) \
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 #define ENERGON_MFMA(acc, a, b) \
@@ -228,28 +292,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
   int64_t m0;
   int32_t n0;
   if (!tile_origin<BM, BN>(tiles_m, tiles_n, m0, n0)) return;
+  // Ragged edges: the last tile of a row / column of tiles is shifted back so that it ends at
+  // M / N (needs M >= BM, N >= BN).  It overlaps its neighbour; both compute bit-identical values
+  // for the shared elements, so no load is clamped and no store is predicated.
+  if (m0 > M - BM) m0 = M - BM;
+  if (n0 > N - BN) n0 = N - BN;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
-  const char* xbase = reinterpret_cast<const char*>(x + (size_t)m0 * K);
-  const char* wbase = reinterpret_cast<const char*>(w + (size_t)n0 * K);
-  uint32_t oa[GA], ob[GB];
-#pragma unroll
-  for (int i = 0; i < GA; ++i) {
-    const int row = (wave + i * NW) * 8 + (lane >> 3), c = (lane & 7) ^ swz(row);
-    const int64_t lim = M - 1 - m0;
-    const uint32_t rr = (uint32_t)(row < lim ? row : lim);
-    oa[i] = (rr * (uint32_t)K + c * 8) * 2u;
-  }
-#pragma unroll
-  for (int i = 0; i < GB; ++i) {
-    const int row = (wave + i * NW) * 8 + (lane >> 3), c = (lane & 7) ^ swz(row);
-    const int32_t lim = N - 1 - n0;
-    const uint32_t rr = (uint32_t)(row < lim ? row : lim);
-    ob[i] = (rr * (uint32_t)K + c * 8) * 2u;
-  }
+  // Row group g (8 rows, 1 KiB of LDS) of a slab is fetched by wavefront g % 4; lane l fetches
+  // the chunk that the swizzle puts in slot l % 8 of row l / 8.  swz(row) depends on row % 16,
+  // i.e. on (l / 8) and the parity of the group = parity of the wavefront: the lane's byte offset
+  // inside its group is the same for every group, and the group bases are scalar.
+  const uint32_t voff = ((uint32_t)(lane >> 3) * (uint32_t)K + (uint32_t)(((lane & 7) ^ swz((wave & 1) * 8 + (lane >> 3))) * 8)) * 2u;
+  const char* xbase = reinterpret_cast<const char*>(x + ((size_t)m0 + 8 * wave) * K);
+  const char* wbase = reinterpret_cast<const char*>(w + ((size_t)n0 + 8 * wave) * K);
+  const size_t gstride = (size_t)(8 * NW) * K * 2;  // bytes between consecutive groups of one wavefront
 
   // LDS byte address of this lane's operand chunk for step ks; tile t adds t*4096 (32 rows).
   // swz depends on row % 16 only and all tile rows are congruent to lrow mod 32.
@@ -270,23 +330,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  constexpr int kStage = (BM + BN) * kChunks;
   const int KT = K / BK;
 
-  // direct-to-LDS load number i of a slab (i < GA: x rows, else W rows) into `stage`
-  auto issue_one = [&](int i, int kt, int stage) {
-    uint4* base = smem + stage * kStage;
-    if (i < GA)
-      __builtin_amdgcn_global_load_lds((gptr_t)(xbase + (size_t)kt * (BK * 2) + oa[i]),
-                                       (lptr_t)(base + (wave + i * NW) * 64), 16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds((gptr_t)(wbase + (size_t)kt * (BK * 2) + ob[i - GA]),
-                                       (lptr_t)(base + BM * kChunks + (wave + (i - GA) * NW) * 64), 16, 0, 0);
-  };
-  auto issue = [&](int kt, int stage) {
-#pragma unroll
-    for (int i = 0; i < GA + GB; ++i) issue_one(i, kt, stage);
-  };
+  // Register-staged slab loads with a two-slab window.  Load i of a slab (i < GA: x rows, else
+  // W rows) fetches this lane's 16-byte chunk of row group (wave + i*NW) into rs[slab & 1][i]; two
+  // slabs later it is written to the LDS buffer that has just been freed.
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 rs0[GA + GB], rs1[GA + GB];
+  uint32_t wraddr = (uint32_t)wave * 1024u + (uint32_t)lane * 16u;  // LDS byte address of group `wave`, buffer 0
+#define ENERGON_GLOAD(dst, i, kt_)                                                                      \
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff),                                 \
+               "s"(((i) < GA ? xbase + (i) * gstride : wbase + ((i) - GA) * gstride) + (size_t)(kt_) * (BK * 2)) \
+               : "memory")
+#define ENERGON_LWRITE(src, i)                                                                          \
+  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(wraddr), "v"(src),                               \
+               "n"(((i) < GA ? (i) * NW * 1024 : BM * 128 + ((i) - GA) * NW * 1024)) : "memory")
 
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];  // operand sets for even / odd steps
 
@@ -319,54 +377,80 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
     ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]);    \
   } while (0)
 
-// step 3: the reads go after MFMAs 1..8 as above, the 16 direct-to-LDS loads of the slab after
-// next go two at a time after MFMAs 9..16
-#define ENERGON_STEP_LOAD(CA_, CB_, NA, NB, nks, kt_, st_)                              \
-  do {                                                                                  \
-    ENERGON_MFMA(acc[0][0], CA_[0], CB_[0]); ENERGON_DS_READ(NA[0], aaddr[nks], 0);      \
-    ENERGON_MFMA(acc[0][1], CA_[0], CB_[1]); ENERGON_DS_READ(NB[0], baddr[nks], 0);      \
-    ENERGON_MFMA(acc[0][2], CA_[0], CB_[2]); ENERGON_DS_READ(NB[1], baddr[nks], 4096);   \
-    ENERGON_MFMA(acc[0][3], CA_[0], CB_[3]); ENERGON_DS_READ(NB[2], baddr[nks], 8192);   \
-    ENERGON_MFMA(acc[1][0], CA_[1], CB_[0]); ENERGON_DS_READ(NB[3], baddr[nks], 12288);  \
-    ENERGON_MFMA(acc[1][1], CA_[1], CB_[1]); ENERGON_DS_READ(NA[1], aaddr[nks], 4096);   \
-    ENERGON_MFMA(acc[1][2], CA_[1], CB_[2]); ENERGON_DS_READ(NA[2], aaddr[nks], 8192);   \
-    ENERGON_MFMA(acc[1][3], CA_[1], CB_[3]); ENERGON_DS_READ(NA[3], aaddr[nks], 12288);  \
-    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]); issue_one(0, kt_, st_); issue_one(1, kt_, st_);   \
-    ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]); issue_one(2, kt_, st_); issue_one(3, kt_, st_);   \
-    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]); issue_one(4, kt_, st_); issue_one(5, kt_, st_);   \
-    ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]); issue_one(6, kt_, st_); issue_one(7, kt_, st_);   \
-    ENERGON_MFMA(acc[3][0], CA_[3], CB_[0]); issue_one(8, kt_, st_); issue_one(9, kt_, st_);   \
-    ENERGON_MFMA(acc[3][1], CA_[3], CB_[1]); issue_one(10, kt_, st_); issue_one(11, kt_, st_); \
-    ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); issue_one(12, kt_, st_); issue_one(13, kt_, st_); \
-    ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]); issue_one(14, kt_, st_); issue_one(15, kt_, st_); \
+// step 3: reads after MFMAs 1..8; after every MFMA one staged chunk (RS[i], fetched two slabs ago)
+// is written to the freed LDS buffer and its register is refilled with the same chunk of slab kl_
+#define ENERGON_STEP_LOAD(CA_, CB_, NA, NB, nks, RS, kl_)                                              \
+  do {                                                                                                  \
+    ENERGON_MFMA(acc[0][0], CA_[0], CB_[0]); ENERGON_DS_READ(NA[0], aaddr[nks], 0);                      \
+    ENERGON_LWRITE(RS[0], 0); ENERGON_GLOAD(RS[0], 0, kl_);                                              \
+    ENERGON_MFMA(acc[0][1], CA_[0], CB_[1]); ENERGON_DS_READ(NB[0], baddr[nks], 0);                      \
+    ENERGON_LWRITE(RS[1], 1); ENERGON_GLOAD(RS[1], 1, kl_);                                              \
+    ENERGON_MFMA(acc[0][2], CA_[0], CB_[2]); ENERGON_DS_READ(NB[1], baddr[nks], 4096);                   \
+    ENERGON_LWRITE(RS[2], 2); ENERGON_GLOAD(RS[2], 2, kl_);                                              \
+    ENERGON_MFMA(acc[0][3], CA_[0], CB_[3]); ENERGON_DS_READ(NB[2], baddr[nks], 8192);                   \
+    ENERGON_LWRITE(RS[3], 3); ENERGON_GLOAD(RS[3], 3, kl_);                                              \
+    ENERGON_MFMA(acc[1][0], CA_[1], CB_[0]); ENERGON_DS_READ(NB[3], baddr[nks], 12288);                  \
+    ENERGON_LWRITE(RS[4], 4); ENERGON_GLOAD(RS[4], 4, kl_);                                              \
+    ENERGON_MFMA(acc[1][1], CA_[1], CB_[1]); ENERGON_DS_READ(NA[1], aaddr[nks], 4096);                   \
+    ENERGON_LWRITE(RS[5], 5); ENERGON_GLOAD(RS[5], 5, kl_);                                              \
+    ENERGON_MFMA(acc[1][2], CA_[1], CB_[2]); ENERGON_DS_READ(NA[2], aaddr[nks], 8192);                   \
+    ENERGON_LWRITE(RS[6], 6); ENERGON_GLOAD(RS[6], 6, kl_);                                              \
+    ENERGON_MFMA(acc[1][3], CA_[1], CB_[3]); ENERGON_DS_READ(NA[3], aaddr[nks], 12288);                  \
+    ENERGON_LWRITE(RS[7], 7); ENERGON_GLOAD(RS[7], 7, kl_);                                              \
+    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]); ENERGON_LWRITE(RS[8], 8); ENERGON_GLOAD(RS[8], 8, kl_);     \
+    ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]); ENERGON_LWRITE(RS[9], 9); ENERGON_GLOAD(RS[9], 9, kl_);     \
+    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]); ENERGON_LWRITE(RS[10], 10); ENERGON_GLOAD(RS[10], 10, kl_); \
+    ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]); ENERGON_LWRITE(RS[11], 11); ENERGON_GLOAD(RS[11], 11, kl_); \
+    ENERGON_MFMA(acc[3][0], CA_[3], CB_[0]); ENERGON_LWRITE(RS[12], 12); ENERGON_GLOAD(RS[12], 12, kl_); \
+    ENERGON_MFMA(acc[3][1], CA_[3], CB_[1]); ENERGON_LWRITE(RS[13], 13); ENERGON_GLOAD(RS[13], 13, kl_); \
+    ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); ENERGON_LWRITE(RS[14], 14); ENERGON_GLOAD(RS[14], 14, kl_); \
+    ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]); ENERGON_LWRITE(RS[15], 15); ENERGON_GLOAD(RS[15], 15, kl_); \
   } while (0)
 
   static_assert(TM == 4 && TN == 4 && GA + GB == 16, "the hand schedule is written for 4 x (128x128)");
 
-  issue(0, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  issue(KT > 1 ? 1 : 0, 1);
+  const int klast = KT - 1;
+  // prologue: slabs 0..3 in flight, 0 and 1 moved to LDS as they land (loads return in order)
+#pragma unroll
+  for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs0[i], i, 0);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs1[i], i, (1 < klast ? 1 : klast));
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { ENERGON_LWRITE(rs0[i], i); ENERGON_GLOAD(rs0[i], i, (2 < klast ? 2 : klast)); }
+  wraddr ^= 0x10000u;
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { ENERGON_LWRITE(rs1[i], i); ENERGON_GLOAD(rs1[i], i, (3 < klast ? 3 : klast)); }
+  wraddr ^= 0x10000u;
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
   ENERGON_READ_SET(fa0, fb0, 0);
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
-  for (int kt = 0; kt < KT; ++kt) {
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 1);
+  // slab kt is consumed from buffer kt&1; after its barrier that buffer receives slab kt+2 from
+  // rs[kt&1], which is refilled with slab kt+4.  Two iterations per trip so rs0/rs1 are static.
+  for (int kt = 0; kt < KT; kt += 2) {
+#define ENERGON_SLAB(RS, kt_)                                                                  \
+    ENERGON_STEP(fa0, fb0, fa1, fb1, 1);                                                       \
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                         \
+    ENERGON_STEP(fa1, fb1, fa0, fb0, 2);                                                       \
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                         \
+    ENERGON_STEP(fa0, fb0, fa1, fb1, 3);                                                       \
+    /* reads of this buffer and the LDS writes of the next slab are done; the chunks of */     \
+    /* slab kt+2 (16 loads older than the newest 16) have landed in RS                  */     \
+    asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");                               \
+    __builtin_amdgcn_s_barrier();                                                              \
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) { aaddr[ks] ^= 0x10000u; baddr[ks] ^= 0x10000u; } \
+    {                                                                                          \
+      const int kl = (kt_) + 4 < KT ? (kt_) + 4 : klast;                                       \
+      ENERGON_STEP_LOAD(fa1, fb1, fa0, fb0, 0, RS, kl);                                        \
+    }                                                                                          \
+    wraddr ^= 0x10000u;                                                                        \
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    ENERGON_STEP(fa1, fb1, fa0, fb0, 2);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 3);
-    // all reads of the current buffer are done, the next slab has landed
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    // Step 3 overlaps the reads of the next slab's step 0 (other buffer) and the loads of slab
-    // kt+2 into the buffer just freed.  Past the end the last slab is fetched again: it lands in
-    // a buffer nobody reads any more, and the final wait below drains it.
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) { aaddr[ks] ^= 0x10000u; baddr[ks] ^= 0x10000u; }
-    const int kload = kt + 2 < KT ? kt + 2 : KT - 1;
-    ENERGON_STEP_LOAD(fa1, fb1, fa0, fb0, 0, kload, kt & 1);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    ENERGON_SLAB(rs0, kt)
+    ENERGON_SLAB(rs1, kt + 1)  // KT is even (K % 128 == 0, checked by the launcher)
+#undef ENERGON_SLAB
   }
   // Drain: outstanding direct-to-LDS loads, and the MFMA pipeline before any accumulator is read
   // (the accumulators are operands so that no read of them can be placed above this statement).
@@ -377,17 +461,23 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
                :
                : "memory");
 #undef ENERGON_STEP_LOAD
+#undef ENERGON_GLOAD
+#undef ENERGON_LWRITE
 #undef ENERGON_STEP
 #undef ENERGON_READ_SET
 
-  store_tile<TM, TN>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane);
+  // The epilogue's per-lane addresses must not be computed (and kept live) above the slab loop,
+  // where every VGPR is spoken for: route the lane id through an ordered asm statement.
+  int lane_e = lane;
+  asm volatile("" : "+v"(lane_e));
+  store_tile_coalesced(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
+                       reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats);
 }
 
 template <typename Kern>
-static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int threads, const bf16_t* x,
+static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int threads, size_t lds, const bf16_t* x,
                                const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y, int64_t M, int32_t N,
                                int32_t K, int epi, hipStream_t s) {
-  const size_t lds = 2 * (size_t)(BM + BN) * kChunks * sizeof(uint4);
   if (!attr_set) {  // idempotent; a race between host threads only repeats the call
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -406,11 +496,16 @@ hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias
   if (M <= 0) return hipSuccess;
   static bool attr_big = false, attr_small = false;
   const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192)  // enough 256x256 tiles for most of the 256 CUs
-    return launch_tiles(gemm_bf16_sched_kernel<256, 256, 2, 2>, attr_big, 256, 256, 256, x, w, bias, res, y, M, N, K,
-                        epi, s);
-  return launch_tiles(gemm_bf16_tile_kernel<128, 128, 2, 2>, attr_small, 128, 128, 256, x, w, bias, res, y, M, N, K,
-                      epi, s);
+  // the 256x256 kernel needs whole tiles to shift at the edges, an even number of slabs, and
+  // enough tiles for most of the 256 CUs
+  if (M >= 256 && N >= 256 && K % 128 == 0 && big_tiles >= 192) {
+    constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
+    constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
+    return launch_tiles(gemm_bf16_sched_kernel<256, 256, 2, 2>, attr_big, 256, 256, 256,
+                        slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, s);
+  }
+  return launch_tiles(gemm_bf16_tile_kernel<128, 128, 2, 2>, attr_small, 128, 128, 256,
+                      2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, s);
 }
 
 }  // namespace energon

@@ -125,6 +125,34 @@ def test_linear(M, N, K, dtype, epi):
         assert np.all(out[M] == 3.0), "row past M was written"
 
 
+@pytest.mark.parametrize("K", [128, 256, 640])
+@pytest.mark.parametrize("epi", [E.EPI_BIAS, E.EPI_BIAS_GELU, E.EPI_BIAS_RESIDUAL])
+def test_linear_large_tile_kernel(K, epi):
+    """Enough 256x256 tiles (14 x 15) to take the hand-scheduled kernel, with M and N that are
+    not multiples of the tile (edge tiles are shifted inwards and overlap their neighbours) and
+    slab counts 2, 4 and 10 (the load pipeline is four slabs deep)."""
+    dtype, M, N = wl.BF16, 3333, 3592
+    rng = np.random.default_rng(K + epi)
+    x = wl.round_to_dtype(rng.standard_normal((M, K)), dtype)
+    w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
+    b = wl.round_to_dtype(rng.standard_normal(N) * 0.5, dtype)
+    r = wl.round_to_dtype(rng.standard_normal((M, N)), dtype)
+    xd, wd, bd, rd = (hz.to_device(a, dtype) for a in (x, w, b, r))
+    yd = torch.full((M + 1, N), 3.0, dtype=xd.dtype, device="cuda")
+    E.energon_linear(xd, wd, bd, rd if epi == E.EPI_BIAS_RESIDUAL else None, yd, epi)
+    ref = x.astype(np.float64) @ w.astype(np.float64).T + b
+    if epi == E.EPI_BIAS_GELU:
+        ref = orc.gelu(ref)
+    if epi == E.EPI_BIAS_RESIDUAL:
+        ref = ref + r
+    out = hz.to_host(yd)
+    assert_close(out[:M], ref, dtype, f"large linear K={K} epi={epi}")
+    assert np.all(out[M] == 3.0), "row past M was written"
+    yd2 = torch.empty_like(yd)
+    E.energon_linear(xd, wd, bd, rd if epi == E.EPI_BIAS_RESIDUAL else None, yd2, epi)
+    assert torch.equal(yd[:M].view(torch.int16), yd2[:M].view(torch.int16)), "not deterministic"
+
+
 def test_linear_residual_in_place():
     dtype, M, N, K = wl.BF16, 130, 256, 128
     rng = np.random.default_rng(5)
