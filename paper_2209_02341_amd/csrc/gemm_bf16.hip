@@ -337,13 +337,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
   // slabs later it is written to the LDS buffer that has just been freed.
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   u32x4 rs0[GA + GB], rs1[GA + GB];
-  uint32_t wraddr = (uint32_t)wave * 1024u + (uint32_t)lane * 16u;  // LDS byte address of group `wave`, buffer 0
+  const uint32_t wa0 = (uint32_t)wave * 1024u + (uint32_t)lane * 16u;  // LDS byte address of group `wave`, buffer 0
+  const uint32_t wa1 = wa0 + 0x10000u;                                    // ... buffer 1
 #define ENERGON_GLOAD(dst, i, kt_)                                                                      \
   asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff),                                 \
                "s"(((i) < GA ? xbase + (i) * gstride : wbase + ((i) - GA) * gstride) + (size_t)(kt_) * (BK * 2)) \
                : "memory")
-#define ENERGON_LWRITE(src, i)                                                                          \
-  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(wraddr), "v"(src),                               \
+#define ENERGON_LWRITE(src, i, WA)                                                                      \
+  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(WA), "v"(src),                                   \
                "n"(((i) < GA ? (i) * NW * 1024 : BM * 128 + ((i) - GA) * NW * 1024)) : "memory")
 
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];  // operand sets for even / odd steps
@@ -360,107 +361,86 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
     ENERGON_DS_READ(FA[3], aaddr[ks], 12288);                             \
   } while (0)
 
-// 16 MFMAs on (CA, CB); the 8 reads of (NA, NB) for step nks go after MFMAs 1..8
-#define ENERGON_STEP(CA_, CB_, NA, NB, nks)                               \
-  do {                                                                    \
-    ENERGON_MFMA(acc[0][0], CA_[0], CB_[0]); ENERGON_DS_READ(NA[0], aaddr[nks], 0);      \
-    ENERGON_MFMA(acc[0][1], CA_[0], CB_[1]); ENERGON_DS_READ(NB[0], baddr[nks], 0);      \
-    ENERGON_MFMA(acc[0][2], CA_[0], CB_[2]); ENERGON_DS_READ(NB[1], baddr[nks], 4096);   \
-    ENERGON_MFMA(acc[0][3], CA_[0], CB_[3]); ENERGON_DS_READ(NB[2], baddr[nks], 8192);   \
-    ENERGON_MFMA(acc[1][0], CA_[1], CB_[0]); ENERGON_DS_READ(NB[3], baddr[nks], 12288);  \
-    ENERGON_MFMA(acc[1][1], CA_[1], CB_[1]); ENERGON_DS_READ(NA[1], aaddr[nks], 4096);   \
-    ENERGON_MFMA(acc[1][2], CA_[1], CB_[2]); ENERGON_DS_READ(NA[2], aaddr[nks], 8192);   \
-    ENERGON_MFMA(acc[1][3], CA_[1], CB_[3]); ENERGON_DS_READ(NA[3], aaddr[nks], 12288);  \
-    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]); ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]);    \
-    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]); ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]);    \
-    ENERGON_MFMA(acc[3][0], CA_[3], CB_[0]); ENERGON_MFMA(acc[3][1], CA_[3], CB_[1]);    \
-    ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]);    \
-  } while (0)
-
-// step 3: reads after MFMAs 1..8; after every MFMA one staged chunk (RS[i], fetched two slabs ago)
-// is written to the freed LDS buffer and its register is refilled with the same chunk of slab kl_
-#define ENERGON_STEP_LOAD(CA_, CB_, NA, NB, nks, RS, kl_)                                              \
+// 16 MFMAs on (CA_, CB_); the 8 reads of (NA, NB) for step nks go after MFMAs 1..8; after MFMAs
+// 9..12 staged chunks i0..i0+3 of RS (fetched 32 loads ago: all but the newest 28 loads have
+// returned) are written to the LDS buffer addressed by WA and refilled with slab kl_.
+#define ENERGON_STEP(CA_, CB_, NA, NB, nks, RS, i0, kl_, WA)                                            \
   do {                                                                                                  \
     ENERGON_MFMA(acc[0][0], CA_[0], CB_[0]); ENERGON_DS_READ(NA[0], aaddr[nks], 0);                      \
-    ENERGON_LWRITE(RS[0], 0); ENERGON_GLOAD(RS[0], 0, kl_);                                              \
     ENERGON_MFMA(acc[0][1], CA_[0], CB_[1]); ENERGON_DS_READ(NB[0], baddr[nks], 0);                      \
-    ENERGON_LWRITE(RS[1], 1); ENERGON_GLOAD(RS[1], 1, kl_);                                              \
     ENERGON_MFMA(acc[0][2], CA_[0], CB_[2]); ENERGON_DS_READ(NB[1], baddr[nks], 4096);                   \
-    ENERGON_LWRITE(RS[2], 2); ENERGON_GLOAD(RS[2], 2, kl_);                                              \
     ENERGON_MFMA(acc[0][3], CA_[0], CB_[3]); ENERGON_DS_READ(NB[2], baddr[nks], 8192);                   \
-    ENERGON_LWRITE(RS[3], 3); ENERGON_GLOAD(RS[3], 3, kl_);                                              \
     ENERGON_MFMA(acc[1][0], CA_[1], CB_[0]); ENERGON_DS_READ(NB[3], baddr[nks], 12288);                  \
-    ENERGON_LWRITE(RS[4], 4); ENERGON_GLOAD(RS[4], 4, kl_);                                              \
     ENERGON_MFMA(acc[1][1], CA_[1], CB_[1]); ENERGON_DS_READ(NA[1], aaddr[nks], 4096);                   \
-    ENERGON_LWRITE(RS[5], 5); ENERGON_GLOAD(RS[5], 5, kl_);                                              \
     ENERGON_MFMA(acc[1][2], CA_[1], CB_[2]); ENERGON_DS_READ(NA[2], aaddr[nks], 8192);                   \
-    ENERGON_LWRITE(RS[6], 6); ENERGON_GLOAD(RS[6], 6, kl_);                                              \
     ENERGON_MFMA(acc[1][3], CA_[1], CB_[3]); ENERGON_DS_READ(NA[3], aaddr[nks], 12288);                  \
-    ENERGON_LWRITE(RS[7], 7); ENERGON_GLOAD(RS[7], 7, kl_);                                              \
-    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]); ENERGON_LWRITE(RS[8], 8); ENERGON_GLOAD(RS[8], 8, kl_);     \
-    ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]); ENERGON_LWRITE(RS[9], 9); ENERGON_GLOAD(RS[9], 9, kl_);     \
-    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]); ENERGON_LWRITE(RS[10], 10); ENERGON_GLOAD(RS[10], 10, kl_); \
-    ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]); ENERGON_LWRITE(RS[11], 11); ENERGON_GLOAD(RS[11], 11, kl_); \
-    ENERGON_MFMA(acc[3][0], CA_[3], CB_[0]); ENERGON_LWRITE(RS[12], 12); ENERGON_GLOAD(RS[12], 12, kl_); \
-    ENERGON_MFMA(acc[3][1], CA_[3], CB_[1]); ENERGON_LWRITE(RS[13], 13); ENERGON_GLOAD(RS[13], 13, kl_); \
-    ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); ENERGON_LWRITE(RS[14], 14); ENERGON_GLOAD(RS[14], 14, kl_); \
-    ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]); ENERGON_LWRITE(RS[15], 15); ENERGON_GLOAD(RS[15], 15, kl_); \
+    asm volatile("s_waitcnt vmcnt(28)" ::: "memory");                                                   \
+    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]);                                                             \
+    ENERGON_LWRITE(RS[(i0) + 0], (i0) + 0, WA); ENERGON_GLOAD(RS[(i0) + 0], (i0) + 0, kl_);               \
+    ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]);                                                             \
+    ENERGON_LWRITE(RS[(i0) + 1], (i0) + 1, WA); ENERGON_GLOAD(RS[(i0) + 1], (i0) + 1, kl_);               \
+    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]);                                                             \
+    ENERGON_LWRITE(RS[(i0) + 2], (i0) + 2, WA); ENERGON_GLOAD(RS[(i0) + 2], (i0) + 2, kl_);               \
+    ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]);                                                             \
+    ENERGON_LWRITE(RS[(i0) + 3], (i0) + 3, WA); ENERGON_GLOAD(RS[(i0) + 3], (i0) + 3, kl_);               \
+    ENERGON_MFMA(acc[3][0], CA_[3], CB_[0]); ENERGON_MFMA(acc[3][1], CA_[3], CB_[1]);                    \
+    ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]);                    \
   } while (0)
 
   static_assert(TM == 4 && TN == 4 && GA + GB == 16, "the hand schedule is written for 4 x (128x128)");
 
   const int klast = KT - 1;
-  // prologue: slabs 0..3 in flight, 0 and 1 moved to LDS as they land (loads return in order)
+  // Prologue.  Afterwards: slab 0 complete in buffer 0, chunks 0..3 of slab 1 in buffer 1,
+  // rs1[4..15] = rest of slab 1, rs0 = slab 2 and rs1[0..3] = slab 3 in flight.
 #pragma unroll
   for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs0[i], i, 0);
 #pragma unroll
   for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs1[i], i, (1 < klast ? 1 : klast));
   asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { ENERGON_LWRITE(rs0[i], i); ENERGON_GLOAD(rs0[i], i, (2 < klast ? 2 : klast)); }
-  wraddr ^= 0x10000u;
+  for (int i = 0; i < 16; ++i) { ENERGON_LWRITE(rs0[i], i, wa0); ENERGON_GLOAD(rs0[i], i, (2 < klast ? 2 : klast)); }
   asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { ENERGON_LWRITE(rs1[i], i); ENERGON_GLOAD(rs1[i], i, (3 < klast ? 3 : klast)); }
-  wraddr ^= 0x10000u;
+  for (int i = 0; i < 4; ++i) { ENERGON_LWRITE(rs1[i], i, wa1); ENERGON_GLOAD(rs1[i], i, (3 < klast ? 3 : klast)); }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   ENERGON_READ_SET(fa0, fb0, 0);
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
-  // slab kt is consumed from buffer kt&1; after its barrier that buffer receives slab kt+2 from
-  // rs[kt&1], which is refilled with slab kt+4.  Two iterations per trip so rs0/rs1 are static.
-  for (int kt = 0; kt < KT; kt += 2) {
-#define ENERGON_SLAB(RS, kt_)                                                                  \
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 1);                                                       \
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                         \
-    ENERGON_STEP(fa1, fb1, fa0, fb0, 2);                                                       \
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                         \
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 3);                                                       \
-    /* reads of this buffer and the LDS writes of the next slab are done; the chunks of */     \
-    /* slab kt+2 (16 loads older than the newest 16) have landed in RS                  */     \
-    asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");                               \
-    __builtin_amdgcn_s_barrier();                                                              \
-    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) { aaddr[ks] ^= 0x10000u; baddr[ks] ^= 0x10000u; } \
-    {                                                                                          \
-      const int kl = (kt_) + 4 < KT ? (kt_) + 4 : klast;                                       \
-      ENERGON_STEP_LOAD(fa1, fb1, fa0, fb0, 0, RS, kl);                                        \
-    }                                                                                          \
-    wraddr ^= 0x10000u;                                                                        \
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    ENERGON_SLAB(rs0, kt)
-    ENERGON_SLAB(rs1, kt + 1)  // KT is even (K % 128 == 0, checked by the launcher)
-#undef ENERGON_SLAB
+  // Slab kt is consumed from buffer kt&1.  The chunks of a slab travel four per step: during
+  // steps 0..2 of slab kt, chunks 4..15 of slab kt+1 go from rs[(kt+1)&1] to the other buffer and
+  // those registers are refilled with slab kt+3; after the barrier (this buffer is free) step 3
+  // moves chunks 0..3 of slab kt+2 from rs[kt&1] into it and refills them with slab kt+4.
+  // LDS traffic is thereby even over the steps: 8 reads + 4 writes per wavefront in each.
+  // Two slabs per trip so that register sets and buffer addresses are static.
+#define ENERGON_SLAB(RC, RN, WC, WN_, kt_)                                                              \
+  {                                                                                                     \
+    const int kl3 = (kt_) + 3 < KT ? (kt_) + 3 : klast, kl4 = (kt_) + 4 < KT ? (kt_) + 4 : klast;       \
+    ENERGON_STEP(fa0, fb0, fa1, fb1, 1, RN, 4, kl3, WN_);                                               \
+    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory"); /* LDS returns in order: the reads are back */  \
+    ENERGON_STEP(fa1, fb1, fa0, fb0, 2, RN, 8, kl3, WN_);                                               \
+    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
+    ENERGON_STEP(fa0, fb0, fa1, fb1, 3, RN, 12, kl3, WN_);                                              \
+    /* this wavefront has read all of the current buffer and written all of slab kt+1 */                \
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                                  \
+    __builtin_amdgcn_s_barrier();                                                                       \
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) { aaddr[ks] ^= 0x10000u; baddr[ks] ^= 0x10000u; }  \
+    ENERGON_STEP(fa1, fb1, fa0, fb0, 0, RC, 0, kl4, WC);                                                \
+    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
   }
-  // Drain: outstanding direct-to-LDS loads, and the MFMA pipeline before any accumulator is read
+  for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0, checked by the launcher)
+    ENERGON_SLAB(rs0, rs1, wa0, wa1, kt)
+    ENERGON_SLAB(rs1, rs0, wa1, wa0, kt + 1)
+  }
+#undef ENERGON_SLAB
+  // Drain: outstanding loads and LDS writes, and the MFMA pipeline before any accumulator is read
   // (the accumulators are operands so that no read of them can be placed above this statement).
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15"
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15"
                : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),
                  "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
                  "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])
                :
                : "memory");
-#undef ENERGON_STEP_LOAD
 #undef ENERGON_GLOAD
 #undef ENERGON_LWRITE
 #undef ENERGON_STEP
