@@ -32,6 +32,13 @@ constexpr int kChunks = BK / 8;   // 16-byte chunks per LDS row
 constexpr int kXcds = 8;
 constexpr int kGroupM = 8;        // row tiles per band
 
+#ifdef ENERGON_GEMM_TIMING  // development aid, never defined in the library build
+__device__ long long* g_gemm_timing;
+#define ENERGON_STAMP(i) do { if (threadIdx.x == 0) g_gemm_timing[blockIdx.x * 4 + (i)] = wall_clock64(); } while (0)
+#else
+#define ENERGON_STAMP(i) do { } while (0)
+#endif
+
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -389,6 +396,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
 
   static_assert(TM == 4 && TN == 4 && GA + GB == 16, "the hand schedule is written for 4 x (128x128)");
 
+  ENERGON_STAMP(0);
   const int klast = KT - 1;
   // Prologue.  Afterwards: slab 0 complete in buffer 0, chunks 0..3 of slab 1 in buffer 1,
   // rs1[4..15] = rest of slab 1, rs0 = slab 2 and rs1[0..3] = slab 3 in flight.
@@ -428,6 +436,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
     ENERGON_STEP(fa1, fb1, fa0, fb0, 0, RC, 0, kl4, WC);                                                \
     asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
   }
+  ENERGON_STAMP(1);
   for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0, checked by the launcher)
     ENERGON_SLAB(rs0, rs1, wa0, wa1, kt)
     ENERGON_SLAB(rs1, rs0, wa1, wa0, kt + 1)
@@ -448,10 +457,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
 
   // The epilogue's per-lane addresses must not be computed (and kept live) above the slab loop,
   // where every VGPR is spoken for: route the lane id through an ordered asm statement.
+  ENERGON_STAMP(2);
   int lane_e = lane;
   asm volatile("" : "+v"(lane_e));
   store_tile_coalesced(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
                        reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats);
+  ENERGON_STAMP(3);
 }
 
 template <typename Kern>
