@@ -267,15 +267,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_tile_kernel(const bf16_
 // The slab loop is written as ordered inline-asm statements so that the issue order is exactly
 // the one below (the compiler otherwise re-serialises LDS reads and MFMAs, and it must not copy
 // or spill a register whose load is still in flight).  One wavefront per SIMD, 128x128 per
-// wavefront.  Per slab of 64 along K, four steps of 16:
-//   step s (0..2): 16 MFMAs on operand set s, the 8 LDS reads of step s+1 slotted after MFMAs 1..8
-//   before step 3: wait for this wavefront's LDS traffic and for the chunks of slab kt+2 (loads
-//              return in order, so "all but the newest 16" suffices), barrier.  The current
-//              buffer is now free.
-//   step 3:    16 MFMAs; after each, one chunk of slab kt+2 goes from its register to the freed
-//              buffer and the register is refilled with the same chunk of slab kt+4; the reads
-//              of the next slab's step 0 (other buffer) are slotted in as above.
-// The barrier thus sits in the shadow of queued MFMAs, and a chunk has two slab times to arrive.
+// wavefront.  Per slab of 64 along K, four steps of 16; every step issues 16 MFMAs and, slotted
+// between them, the 8 LDS reads of the next step's operands, 4 global loads and 4 LDS writes
+// (see ENERGON_STEP and ENERGON_SLAB).  One barrier per slab, in the shadow of queued MFMAs; a
+// fetched chunk has two slab times to arrive.
+// What the compiler cannot see inside asm statements it cannot guard: this code itself keeps
+// the wait states between an MFMA and the first read of its result (end of the slab loop) and
+// between a register write and an MFMA reading it (accumulator zeroing).
 #define ENERGON_DS_READ(dst, addr, off) \
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 #define ENERGON_MFMA(acc, a, b) \
@@ -336,6 +334,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  // The compiler sees no MFMA (they are inside asm statements) and so adds no wait states between
+  // a register write and an MFMA that reads it: have the zeros written here, before the prologue.
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
 
   const int KT = K / BK;
 
@@ -347,7 +351,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
   const uint32_t wa0 = (uint32_t)wave * 1024u + (uint32_t)lane * 16u;  // LDS byte address of group `wave`, buffer 0
   const uint32_t wa1 = wa0 + 0x10000u;                                    // ... buffer 1
 #define ENERGON_GLOAD(dst, i, kt_)                                                                      \
-  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff),                                 \
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff),                                \
                "s"(((i) < GA ? xbase + (i) * gstride : wbase + ((i) - GA) * gstride) + (size_t)(kt_) * (BK * 2)) \
                : "memory")
 #define ENERGON_LWRITE(src, i, WA)                                                                      \
@@ -368,88 +372,101 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
     ENERGON_DS_READ(FA[3], aaddr[ks], 12288);                             \
   } while (0)
 
-// 16 MFMAs on (CA_, CB_); the 8 reads of (NA, NB) for step nks go after MFMAs 1..8; after MFMAs
-// 9..12 staged chunks i0..i0+3 of RS (fetched 32 loads ago: all but the newest 28 loads have
-// returned) are written to the LDS buffer addressed by WA and refilled with slab kl_.
-#define ENERGON_STEP(CA_, CB_, NA, NB, nks, RS, i0, kl_, WA)                                            \
+// One step: 16 MFMAs on (CA_, CB_) with, slotted between them,
+//  * the 8 LDS reads of (NA, NB) for step nks (after MFMAs 1..8);
+//  * after MFMAs 5..8, the reload of the four staged registers RL[il..il+3] with slab kl_.  Their
+//    previous contents were written to LDS in the step before; an LDS write reads its data
+//    registers only when it executes, so they may be overwritten only once that write has
+//    completed: LDS operations complete in order, hence the lgkmcnt(4) after the first 4 reads;
+//  * after MFMAs 9..12, the write of RW[iw..iw+3] (fetched 32 loads ago: loads return in order,
+//    so all but the newest 28 have landed) to the LDS buffer addressed by WA.
+#define ENERGON_STEP(CA_, CB_, NA, NB, nks, RL, il, kl_, RW, iw, WA)                                    \
   do {                                                                                                  \
     ENERGON_MFMA(acc[0][0], CA_[0], CB_[0]); ENERGON_DS_READ(NA[0], aaddr[nks], 0);                      \
     ENERGON_MFMA(acc[0][1], CA_[0], CB_[1]); ENERGON_DS_READ(NB[0], baddr[nks], 0);                      \
     ENERGON_MFMA(acc[0][2], CA_[0], CB_[2]); ENERGON_DS_READ(NB[1], baddr[nks], 4096);                   \
     ENERGON_MFMA(acc[0][3], CA_[0], CB_[3]); ENERGON_DS_READ(NB[2], baddr[nks], 8192);                   \
+    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
     ENERGON_MFMA(acc[1][0], CA_[1], CB_[0]); ENERGON_DS_READ(NB[3], baddr[nks], 12288);                  \
+    ENERGON_GLOAD(RL[(il) + 0], (il) + 0, kl_);                                                          \
     ENERGON_MFMA(acc[1][1], CA_[1], CB_[1]); ENERGON_DS_READ(NA[1], aaddr[nks], 4096);                   \
+    ENERGON_GLOAD(RL[(il) + 1], (il) + 1, kl_);                                                          \
     ENERGON_MFMA(acc[1][2], CA_[1], CB_[2]); ENERGON_DS_READ(NA[2], aaddr[nks], 8192);                   \
+    ENERGON_GLOAD(RL[(il) + 2], (il) + 2, kl_);                                                          \
     ENERGON_MFMA(acc[1][3], CA_[1], CB_[3]); ENERGON_DS_READ(NA[3], aaddr[nks], 12288);                  \
+    ENERGON_GLOAD(RL[(il) + 3], (il) + 3, kl_);                                                          \
     asm volatile("s_waitcnt vmcnt(28)" ::: "memory");                                                   \
-    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]);                                                             \
-    ENERGON_LWRITE(RS[(i0) + 0], (i0) + 0, WA); ENERGON_GLOAD(RS[(i0) + 0], (i0) + 0, kl_);               \
-    ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]);                                                             \
-    ENERGON_LWRITE(RS[(i0) + 1], (i0) + 1, WA); ENERGON_GLOAD(RS[(i0) + 1], (i0) + 1, kl_);               \
-    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]);                                                             \
-    ENERGON_LWRITE(RS[(i0) + 2], (i0) + 2, WA); ENERGON_GLOAD(RS[(i0) + 2], (i0) + 2, kl_);               \
-    ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]);                                                             \
-    ENERGON_LWRITE(RS[(i0) + 3], (i0) + 3, WA); ENERGON_GLOAD(RS[(i0) + 3], (i0) + 3, kl_);               \
+    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]); ENERGON_LWRITE(RW[(iw) + 0], (iw) + 0, WA);                 \
+    ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]); ENERGON_LWRITE(RW[(iw) + 1], (iw) + 1, WA);                 \
+    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]); ENERGON_LWRITE(RW[(iw) + 2], (iw) + 2, WA);                 \
+    ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]); ENERGON_LWRITE(RW[(iw) + 3], (iw) + 3, WA);                 \
     ENERGON_MFMA(acc[3][0], CA_[3], CB_[0]); ENERGON_MFMA(acc[3][1], CA_[3], CB_[1]);                    \
     ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]);                    \
   } while (0)
 
   static_assert(TM == 4 && TN == 4 && GA + GB == 16, "the hand schedule is written for 4 x (128x128)");
 
-  ENERGON_STAMP(0);
   const int klast = KT - 1;
   // Prologue.  Afterwards: slab 0 complete in buffer 0, chunks 0..3 of slab 1 in buffer 1,
-  // rs1[4..15] = rest of slab 1, rs0 = slab 2 and rs1[0..3] = slab 3 in flight.
+  // rs1[4..15] = rest of slab 1 (landed), rs0 = slab 2 in flight, rs1[0..3] free (their LDS
+  // writes have completed).
 #pragma unroll
   for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs0[i], i, 0);
 #pragma unroll
   for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs1[i], i, (1 < klast ? 1 : klast));
   asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { ENERGON_LWRITE(rs0[i], i, wa0); ENERGON_GLOAD(rs0[i], i, (2 < klast ? 2 : klast)); }
-  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  for (int i = 0; i < 16; ++i) ENERGON_LWRITE(rs0[i], i, wa0);
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // slab 1 landed; rs0 has been read
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { ENERGON_LWRITE(rs1[i], i, wa1); ENERGON_GLOAD(rs1[i], i, (3 < klast ? 3 : klast)); }
+  for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs0[i], i, (2 < klast ? 2 : klast));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) ENERGON_LWRITE(rs1[i], i, wa1);
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   ENERGON_READ_SET(fa0, fb0, 0);
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
-  // Slab kt is consumed from buffer kt&1.  The chunks of a slab travel four per step: during
-  // steps 0..2 of slab kt, chunks 4..15 of slab kt+1 go from rs[(kt+1)&1] to the other buffer and
-  // those registers are refilled with slab kt+3; after the barrier (this buffer is free) step 3
-  // moves chunks 0..3 of slab kt+2 from rs[kt&1] into it and refills them with slab kt+4.
-  // LDS traffic is thereby even over the steps: 8 reads + 4 writes per wavefront in each.
-  // Two slabs per trip so that register sets and buffer addresses are static.
+  // Slab kt is consumed from buffer kt&1.  RN = rs[(kt+1)&1] holds slab kt+1: its chunks 0..3
+  // reached the other buffer in the previous slab's step 3, chunks 4..15 follow in steps 0..2,
+  // four per step, and each group of four registers is refilled with slab kt+3 one step after
+  // it was written out.  After the barrier this buffer is free, and step 3 moves chunks 0..3 of
+  // slab kt+2 from RC = rs[kt&1] into it.  LDS traffic is thereby even over the steps: 8 reads
+  // + 4 writes per wavefront in each.  Two slabs per trip so that register sets and buffer
+  // addresses are static.
 #define ENERGON_SLAB(RC, RN, WC, WN_, kt_)                                                              \
   {                                                                                                     \
-    const int kl3 = (kt_) + 3 < KT ? (kt_) + 3 : klast, kl4 = (kt_) + 4 < KT ? (kt_) + 4 : klast;       \
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 1, RN, 4, kl3, WN_);                                               \
+    const int kl3 = (kt_) + 3 < KT ? (kt_) + 3 : klast;                                                 \
+    ENERGON_STEP(fa0, fb0, fa1, fb1, 1, RN, 0, kl3, RN, 4, WN_);                                        \
     asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory"); /* LDS returns in order: the reads are back */  \
-    ENERGON_STEP(fa1, fb1, fa0, fb0, 2, RN, 8, kl3, WN_);                                               \
+    ENERGON_STEP(fa1, fb1, fa0, fb0, 2, RN, 4, kl3, RN, 8, WN_);                                        \
     asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 3, RN, 12, kl3, WN_);                                              \
+    ENERGON_STEP(fa0, fb0, fa1, fb1, 3, RN, 8, kl3, RN, 12, WN_);                                       \
     /* this wavefront has read all of the current buffer and written all of slab kt+1 */                \
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                                  \
     __builtin_amdgcn_s_barrier();                                                                       \
     _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) { aaddr[ks] ^= 0x10000u; baddr[ks] ^= 0x10000u; }  \
-    ENERGON_STEP(fa1, fb1, fa0, fb0, 0, RC, 0, kl4, WC);                                                \
+    ENERGON_STEP(fa1, fb1, fa0, fb0, 0, RN, 12, kl3, RC, 0, WC);                                        \
     asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
   }
-  ENERGON_STAMP(1);
   for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0, checked by the launcher)
     ENERGON_SLAB(rs0, rs1, wa0, wa1, kt)
     ENERGON_SLAB(rs1, rs0, wa1, wa0, kt + 1)
+    // Last trip only: let the MFMA pipeline run empty before control leaves the loop.  Past this
+    // point the compiler moves accumulators between registers as it pleases, and it knows of no
+    // MFMA in flight (they are inside asm statements), so it would add none of the wait states
+    // that a read of a matrix-core result needs.
+    asm volatile("s_cmp_lt_i32 %0, %1\n\t"
+                 "s_cbranch_scc1 .Lenergon_more_%=\n\t"
+                 "s_nop 15\n\ts_nop 15\n\ts_nop 15\n"
+                 ".Lenergon_more_%=:"
+                 :
+                 : "s"(kt + 2), "s"(KT)
+                 : "scc", "memory");
   }
 #undef ENERGON_SLAB
-  // Drain: outstanding loads and LDS writes, and the MFMA pipeline before any accumulator is read
-  // (the accumulators are operands so that no read of them can be placed above this statement).
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15"
-               : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]), "+a"(acc[1][1]),
-                 "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
-                 "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3])
-               :
-               : "memory");
+  // Outstanding loads (the clamped refetches of the last slabs) and LDS writes.
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #undef ENERGON_GLOAD
 #undef ENERGON_LWRITE
 #undef ENERGON_STEP
@@ -489,7 +506,10 @@ hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias
   const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
   // the 256x256 kernel needs whole tiles to shift at the edges, an even number of slabs, and
   // enough tiles for most of the 256 CUs
-  if (M >= 256 && N >= 256 && K % 128 == 0 && big_tiles >= 192) {
+  // (shifted edge tiles overlap their neighbours: with the residual aliasing y, an overlapped
+  // element could be read after the neighbour's write, so that case needs whole tiles)
+  const bool overlap_safe = res != y || (M % 256 == 0 && N % 256 == 0);
+  if (M >= 256 && N >= 256 && K % 128 == 0 && big_tiles >= 192 && overlap_safe) {
     constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
     constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
     return launch_tiles(gemm_bf16_sched_kernel<256, 256, 2, 2>, attr_big, 256, 256, 256,
