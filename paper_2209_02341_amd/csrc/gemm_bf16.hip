@@ -88,17 +88,19 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const bf
   }
 }
 
-// Epilogue of one wavefront's 128x128 tile through LDS, for tiles that lie wholly inside the
-// matrix.  The accumulators go to LDS as fp32 (64 rows at a time, rows padded to 136 floats so
-// the two half-wavefronts of a store hit different banks); each lane then owns 8 consecutive
-// columns of a row: bias, GeLU / residual are applied there in fp32 and the row segment leaves as
-// one 16-byte store, 16 lanes per 256-byte row segment.  One rounding, full-line writes.
-constexpr int kEpiLd = 136;
+// Epilogue of one wavefront's 128x128 tile (8 x 8 accumulator tiles of 16x16; in each the lane
+// holds column lane % 16, rows 4 * (lane / 16) + e) through LDS, for tiles that lie wholly
+// inside the matrix.  The accumulators go to LDS as fp32, 64 rows at a time, rows padded to 132
+// floats so that the four lane groups of a store (4 rows apart) hit different banks; each lane
+// then owns 8 consecutive columns of a row: bias, GeLU / residual are applied there in fp32 and the
+// row segment leaves as one 16-byte store, 16 lanes per 256-byte row segment.  One rounding,
+// full-line writes.
+constexpr int kEpiLd = 132;
 constexpr int kEpiWaveFloats = 64 * kEpiLd;
-__device__ __forceinline__ void store_tile_coalesced(const f32x16 (&acc)[4][4], const bf16_t* __restrict__ bias,
+__device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], const bf16_t* __restrict__ bias,
                                                      const bf16_t* res, bf16_t* y, int32_t N, int epi, int64_t mw,
                                                      int32_t nw, int lane, float* stage) {
-  const int lrow = lane & 31, lhalf = lane >> 5;
+  const int lrow = lane & 15, lq = lane >> 4;
   const int rr = lane >> 4, c8 = (lane & 15) * 8;
   float bv[8];
   if (bias != nullptr) {
@@ -113,12 +115,12 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x16 (&acc)[4][4], 
   for (int pass = 0; pass < 2; ++pass) {
     __syncthreads();  // the slab buffers (first pass) / the previous pass's rows are no longer read
 #pragma unroll
-    for (int ii = 0; ii < 2; ++ii)
+    for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 8; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          stage[(ii * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3)) * kEpiLd + j * 32 + lrow] = acc[pass * 2 + ii][j][e];
+        for (int e = 0; e < 4; ++e)
+          stage[(ii * 16 + lq * 4 + e) * kEpiLd + j * 16 + lrow] = acc[pass * 4 + ii][j][e];
     __syncthreads();
 #pragma unroll 4
     for (int it = 0; it < 16; ++it) {
@@ -267,17 +269,23 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_tile_kernel(const bf16_
 // The slab loop is written as ordered inline-asm statements so that the issue order is exactly
 // the one below (the compiler otherwise re-serialises LDS reads and MFMAs, and it must not copy
 // or spill a register whose load is still in flight).  One wavefront per SIMD, 128x128 per
-// wavefront.  Per slab of 64 along K, four steps of 16; every step issues 16 MFMAs and, slotted
-// between them, the 8 LDS reads of the next step's operands, 4 global loads and 4 LDS writes
-// (see ENERGON_STEP and ENERGON_SLAB).  One barrier per slab, in the shadow of queued MFMAs; a
-// fetched chunk has two slab times to arrive.
+// wavefront = 8 x 8 tiles of v_mfma_f32_16x16x32_bf16 (measured on random operands under the
+// chip's power limit: 16 % more flops per second than the 32x32x16 form).
+// A slab of 64 along K is two MFMA steps of 32; a step is four quadrants of 16 MFMAs, one half
+// (4 fragments) of the A operands against one half of the B operands.  There is ONE set of
+// operand registers: the quadrants are walked in an order in which each half is released at
+// least one quadrant before its successor is needed,
+//   even step:  (aL,bL) (aL,bH) (aH,bH) (aH,bL)      odd step:  (aL,bH) (aL,bL) (aH,bL) (aH,bH)
+// and every quadrant carries the 4 LDS reads that refill the half released last, 2 global loads
+// and 2 LDS writes of staged chunks (see ENERGON_QUAD and ENERGON_SLAB): LDS and memory traffic
+// is even over the loop.  One barrier per slab; a fetched chunk has 1.75 slab times to arrive.
 // What the compiler cannot see inside asm statements it cannot guard: this code itself keeps
 // the wait states between an MFMA and the first read of its result (end of the slab loop) and
 // between a register write and an MFMA reading it (accumulator zeroing).
 #define ENERGON_DS_READ(dst, addr, off) \
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
 #define ENERGON_MFMA(acc, a, b) \
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b))
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b))
 
 template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16_t* __restrict__ x,
@@ -288,10 +296,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
                                                                     int32_t tiles_n) {
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
-  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int TM = WTM / 16, TN = WTN / 16;
   constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "row groups must divide evenly");
   static_assert((BM + BN) * 128 == 65536, "stage stride is assumed to be 64 KiB");
+  static_assert(TM == 8 && TN == 8 && GA + GB == 16, "the hand schedule is written for 4 x (128x128)");
   extern __shared__ uint4 smem[];  // [2][BM + BN][kChunks]
 
   int64_t m0;
@@ -302,38 +311,31 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
   // for the shared elements, so no load is clamped and no store is predicated.
   if (m0 > M - BM) m0 = M - BM;
   if (n0 > N - BN) n0 = N - BN;
+  ENERGON_STAMP(0);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
-  // Row group g (8 rows, 1 KiB of LDS) of a slab is fetched by wavefront g % 4; lane l fetches
-  // the chunk that the swizzle puts in slot l % 8 of row l / 8.  swz(row) depends on row % 16,
-  // i.e. on (l / 8) and the parity of the group = parity of the wavefront: the lane's byte offset
-  // inside its group is the same for every group, and the group bases are scalar.
-  const uint32_t voff = ((uint32_t)(lane >> 3) * (uint32_t)K + (uint32_t)(((lane & 7) ^ swz((wave & 1) * 8 + (lane >> 3))) * 8)) * 2u;
-  const char* xbase = reinterpret_cast<const char*>(x + ((size_t)m0 + 8 * wave) * K);
-  const char* wbase = reinterpret_cast<const char*>(w + ((size_t)n0 + 8 * wave) * K);
-  const size_t gstride = (size_t)(8 * NW) * K * 2;  // bytes between consecutive groups of one wavefront
-
-  // LDS byte address of this lane's operand chunk for step ks; tile t adds t*4096 (32 rows).
-  // swz depends on row % 16 only and all tile rows are congruent to lrow mod 32.
-  const int lrow = lane & 31, lhalf = lane >> 5;
-  uint32_t aaddr[4], baddr[4];
+  // MFMA operand fragment of a 16-row tile for the step ks (32 along K = chunks 4 ks .. 4 ks + 3
+  // of the slab row): lane l holds row l % 16, chunk 4 ks + l / 16.  LDS byte address of that
+  // chunk for tile 0; tile t adds t * 2048 (16 rows), and swz depends on row % 16 only.
+  const int lrow = lane & 15, lq = lane >> 4;
+  uint32_t aaddr[2], baddr[2];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    const uint32_t chunk = (uint32_t)((ks * 2 + lhalf) ^ swz(lrow)) * 16u;
+  for (int ks = 0; ks < 2; ++ks) {
+    const uint32_t chunk = (uint32_t)((ks * 4 + lq) ^ swz(lrow)) * 16u;
     aaddr[ks] = (uint32_t)(wm0 + lrow) * 128u + chunk;
     baddr[ks] = (uint32_t)(BM + wn0 + lrow) * 128u + chunk;
   }
 
-  f32x16 acc[TM][TN];
+  f32x4 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
   // The compiler sees no MFMA (they are inside asm statements) and so adds no wait states between
   // a register write and an MFMA that reads it: have the zeros written here, before the prologue.
 #pragma unroll
@@ -343,115 +345,115 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
 
   const int KT = K / BK;
 
-  // Register-staged slab loads with a two-slab window.  Load i of a slab (i < GA: x rows, else
-  // W rows) fetches this lane's 16-byte chunk of row group (wave + i*NW) into rs[slab & 1][i]; two
-  // slabs later it is written to the LDS buffer that has just been freed.
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  u32x4 rs0[GA + GB], rs1[GA + GB];
-  const uint32_t wa0 = (uint32_t)wave * 1024u + (uint32_t)lane * 16u;  // LDS byte address of group `wave`, buffer 0
-  const uint32_t wa1 = wa0 + 0x10000u;                                    // ... buffer 1
-#define ENERGON_GLOAD(dst, i, kt_)                                                                      \
-  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff),                                \
-               "s"(((i) < GA ? xbase + (i) * gstride : wbase + ((i) - GA) * gstride) + (size_t)(kt_) * (BK * 2)) \
-               : "memory")
-#define ENERGON_LWRITE(src, i, WA)                                                                      \
-  asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(WA), "v"(src),                                   \
-               "n"(((i) < GA ? (i) * NW * 1024 : BM * 128 + ((i) - GA) * NW * 1024)) : "memory")
+  // Slab loads go straight from global memory to LDS (global_load_lds_dwordx4: no staging
+  // register, no LDS store instruction; LDS stores from registers would occupy the LDS pipeline
+  // longer than all the operand reads).  One instruction moves a row group: 8 rows x 128 bytes =
+  // 1 KiB of LDS in lane order, lane l landing in slot l % 8 of row l / 8 and fetching the chunk
+  // that the swizzle puts there.  The 64 row groups of a slab fall in four classes by the operand
+  // half that reads them -- AL / AH: x rows 0..63 / 64..127 of each wavefront row, BL / BH likewise
+  // for W -- and every wavefront moves 4 groups of each class, of its own parity (swz(row) depends
+  // on row % 16 = 8 * (group parity) + l / 8, so one per-lane offset serves all its groups).
+  const uint32_t voff = ((uint32_t)(lane >> 3) * (uint32_t)K + (uint32_t)(((lane & 7) ^ swz((wave & 1) * 8 + (lane >> 3))) * 8)) * 2u;
+  const char* gsrc[4][4];  // [class AL, BH, BL, AH][j]: global address of the group's first row, slab 0
+  uint32_t ldst[4][4];     // its LDS byte offset in buffer 0
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool is_a = (c == 0 || c == 3), high = (c == 1 || c == 3);
+      const int gl = 2 * ((wave >> 1) * 4 + j) + (wave & 1);           // 0..15 within the class
+      const int g = gl + (gl >= 8 ? 8 : 0) + (high ? 8 : 0);            // row group within the operand's 32
+      gsrc[c][j] = reinterpret_cast<const char*>((is_a ? x + (size_t)m0 * K : w + (size_t)n0 * K) + (size_t)(8 * g) * K);
+      ldst[c][j] = (uint32_t)((is_a ? 0 : BM * 128) + g * 1024);
+    }
+#define ENERGON_DMA(c, j, kt_, buf)                                                                     \
+  __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[c][j] + (size_t)(kt_) * (BK * 2) + voff),              \
+                                   (lptr_t)(reinterpret_cast<char*>(smem) + (buf) * 0x10000 + ldst[c][j]), 16, 0, 0)
 
-  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];  // operand sets for even / odd steps
-
-#define ENERGON_READ_SET(FA, FB, ks)                                      \
+  bf16x8 fa[TM], fb[TN];  // the operand fragments: x-row tiles, W-row tiles
+#define ENERGON_RA(t, ks) ENERGON_DS_READ(fa[t], aaddr[ks], (t) * 2048)
+#define ENERGON_RB(t, ks) ENERGON_DS_READ(fb[t], baddr[ks], (t) * 2048)
+#define ENERGON_MF(i, j) ENERGON_MFMA(acc[i][j], fa[i], fb[j])
+#define ENERGON_NONE do { } while (0)
+// Wait for this wavefront's LDS reads and for all but its newest `n` slab loads, then meet the
+// other wavefronts: what they have read may now be overwritten, what they have fetched may be read.
+#define ENERGON_SYNC(n)                                                   \
   do {                                                                    \
-    ENERGON_DS_READ(FA[0], aaddr[ks], 0);                                 \
-    ENERGON_DS_READ(FB[0], baddr[ks], 0);                                 \
-    ENERGON_DS_READ(FB[1], baddr[ks], 4096);                              \
-    ENERGON_DS_READ(FB[2], baddr[ks], 8192);                              \
-    ENERGON_DS_READ(FB[3], baddr[ks], 12288);                             \
-    ENERGON_DS_READ(FA[1], aaddr[ks], 4096);                              \
-    ENERGON_DS_READ(FA[2], aaddr[ks], 8192);                              \
-    ENERGON_DS_READ(FA[3], aaddr[ks], 12288);                             \
+    asm volatile("s_waitcnt vmcnt(" #n ") lgkmcnt(0)" ::: "memory");      \
+    __builtin_amdgcn_s_barrier();                                         \
   } while (0)
 
-// One step: 16 MFMAs on (CA_, CB_) with, slotted between them,
-//  * the 8 LDS reads of (NA, NB) for step nks (after MFMAs 1..8);
-//  * after MFMAs 5..8, the reload of the four staged registers RL[il..il+3] with slab kl_.  Their
-//    previous contents were written to LDS in the step before; an LDS write reads its data
-//    registers only when it executes, so they may be overwritten only once that write has
-//    completed: LDS operations complete in order, hence the lgkmcnt(4) after the first 4 reads;
-//  * after MFMAs 9..12, the write of RW[iw..iw+3] (fetched 32 loads ago: loads return in order,
-//    so all but the newest 28 have landed) to the LDS buffer addressed by WA.
-#define ENERGON_STEP(CA_, CB_, NA, NB, nks, RL, il, kl_, RW, iw, WA)                                    \
-  do {                                                                                                  \
-    ENERGON_MFMA(acc[0][0], CA_[0], CB_[0]); ENERGON_DS_READ(NA[0], aaddr[nks], 0);                      \
-    ENERGON_MFMA(acc[0][1], CA_[0], CB_[1]); ENERGON_DS_READ(NB[0], baddr[nks], 0);                      \
-    ENERGON_MFMA(acc[0][2], CA_[0], CB_[2]); ENERGON_DS_READ(NB[1], baddr[nks], 4096);                   \
-    ENERGON_MFMA(acc[0][3], CA_[0], CB_[3]); ENERGON_DS_READ(NB[2], baddr[nks], 8192);                   \
-    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
-    ENERGON_MFMA(acc[1][0], CA_[1], CB_[0]); ENERGON_DS_READ(NB[3], baddr[nks], 12288);                  \
-    ENERGON_GLOAD(RL[(il) + 0], (il) + 0, kl_);                                                          \
-    ENERGON_MFMA(acc[1][1], CA_[1], CB_[1]); ENERGON_DS_READ(NA[1], aaddr[nks], 4096);                   \
-    ENERGON_GLOAD(RL[(il) + 1], (il) + 1, kl_);                                                          \
-    ENERGON_MFMA(acc[1][2], CA_[1], CB_[2]); ENERGON_DS_READ(NA[2], aaddr[nks], 8192);                   \
-    ENERGON_GLOAD(RL[(il) + 2], (il) + 2, kl_);                                                          \
-    ENERGON_MFMA(acc[1][3], CA_[1], CB_[3]); ENERGON_DS_READ(NA[3], aaddr[nks], 12288);                  \
-    ENERGON_GLOAD(RL[(il) + 3], (il) + 3, kl_);                                                          \
-    asm volatile("s_waitcnt vmcnt(28)" ::: "memory");                                                   \
-    ENERGON_MFMA(acc[2][0], CA_[2], CB_[0]); ENERGON_LWRITE(RW[(iw) + 0], (iw) + 0, WA);                 \
-    ENERGON_MFMA(acc[2][1], CA_[2], CB_[1]); ENERGON_LWRITE(RW[(iw) + 1], (iw) + 1, WA);                 \
-    ENERGON_MFMA(acc[2][2], CA_[2], CB_[2]); ENERGON_LWRITE(RW[(iw) + 2], (iw) + 2, WA);                 \
-    ENERGON_MFMA(acc[2][3], CA_[2], CB_[3]); ENERGON_LWRITE(RW[(iw) + 3], (iw) + 3, WA);                 \
-    ENERGON_MFMA(acc[3][0], CA_[3], CB_[0]); ENERGON_MFMA(acc[3][1], CA_[3], CB_[1]);                    \
-    ENERGON_MFMA(acc[3][2], CA_[3], CB_[2]); ENERGON_MFMA(acc[3][3], CA_[3], CB_[3]);                    \
+// One quadrant: the 16 MFMAs of A tiles ai..ai+3 against B tiles bj..bj+3 with, slotted between
+// them, four LDS reads R0..R3 (fragments of a half that the previous quadrants have released) and
+// up to four slab loads D0..D3; TAIL is the synchronisation that ends it (the reads are back on
+// leaving in any case).
+#define ENERGON_QUAD(ai, bj, R0, R1, R2, R3, D0, D1, D2, D3, TAIL)                              \
+  do {                                                                                         \
+    ENERGON_MF(ai + 0, bj + 0); R0; ENERGON_MF(ai + 0, bj + 1); R1;                             \
+    ENERGON_MF(ai + 0, bj + 2); R2; ENERGON_MF(ai + 0, bj + 3); R3;                             \
+    ENERGON_MF(ai + 1, bj + 0); D0; ENERGON_MF(ai + 1, bj + 1); D1;                             \
+    ENERGON_MF(ai + 1, bj + 2); D2; ENERGON_MF(ai + 1, bj + 3); D3;                             \
+    ENERGON_MF(ai + 2, bj + 0); ENERGON_MF(ai + 2, bj + 1); ENERGON_MF(ai + 2, bj + 2); ENERGON_MF(ai + 2, bj + 3); \
+    ENERGON_MF(ai + 3, bj + 0); ENERGON_MF(ai + 3, bj + 1); ENERGON_MF(ai + 3, bj + 2); ENERGON_MF(ai + 3, bj + 3); \
+    TAIL;                                                                                      \
   } while (0)
-
-  static_assert(TM == 4 && TN == 4 && GA + GB == 16, "the hand schedule is written for 4 x (128x128)");
+#define ENERGON_READS_BACK asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
 
   const int klast = KT - 1;
-  // Prologue.  Afterwards: slab 0 complete in buffer 0, chunks 0..3 of slab 1 in buffer 1,
-  // rs1[4..15] = rest of slab 1 (landed), rs0 = slab 2 in flight, rs1[0..3] free (their LDS
-  // writes have completed).
+  // Prologue: slab 0 into buffer 0 (waited for), slab 1 into buffer 1 (in flight), the fragments
+  // of the first quadrant in registers.  Load order within a slab is AL, BH, BL, AH throughout.
 #pragma unroll
-  for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs0[i], i, 0);
+  for (int c = 0; c < 4; ++c)
 #pragma unroll
-  for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs1[i], i, (1 < klast ? 1 : klast));
+    for (int j = 0; j < 4; ++j) ENERGON_DMA(c, j, 0, 0);
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ENERGON_DMA(c, j, (1 < klast ? 1 : klast), 1);
   asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-#pragma unroll
-  for (int i = 0; i < 16; ++i) ENERGON_LWRITE(rs0[i], i, wa0);
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // slab 1 landed; rs0 has been read
-#pragma unroll
-  for (int i = 0; i < 16; ++i) ENERGON_GLOAD(rs0[i], i, (2 < klast ? 2 : klast));
-#pragma unroll
-  for (int i = 0; i < 4; ++i) ENERGON_LWRITE(rs1[i], i, wa1);
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
-  ENERGON_READ_SET(fa0, fb0, 0);
+  ENERGON_RA(0, 0); ENERGON_RA(1, 0); ENERGON_RA(2, 0); ENERGON_RA(3, 0);
+  ENERGON_RB(0, 0); ENERGON_RB(1, 0); ENERGON_RB(2, 0); ENERGON_RB(3, 0);
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  ENERGON_STAMP(1);
 
-  // Slab kt is consumed from buffer kt&1.  RN = rs[(kt+1)&1] holds slab kt+1: its chunks 0..3
-  // reached the other buffer in the previous slab's step 3, chunks 4..15 follow in steps 0..2,
-  // four per step, and each group of four registers is refilled with slab kt+3 one step after
-  // it was written out.  After the barrier this buffer is free, and step 3 moves chunks 0..3 of
-  // slab kt+2 from RC = rs[kt&1] into it.  LDS traffic is thereby even over the steps: 8 reads
-  // + 4 writes per wavefront in each.  Two slabs per trip so that register sets and buffer
-  // addresses are static.
-#define ENERGON_SLAB(RC, RN, WC, WN_, kt_)                                                              \
+  // Slab kt is consumed from buffer kt & 1 while slab kt+1 (other buffer) is landing.  Quadrants
+  // 2, 3, 4, 5 hold the last reads of the classes AL, BH, BL, AH of slab kt; the barrier that
+  // ends each of them frees that class's rows in the current buffer, and the loads of the same
+  // class of slab kt+2 follow in the next two quadrants.  Reads of slab kt+1 start in quadrant 6
+  // (AL), 7 (BL), then 0 (BH) and 1 (AH) of the next slab: the barriers ending quadrants 5, 6 and
+  // 0 are preceded by waits for exactly those classes (loads return in order; the count is the
+  // number of loads issued after the class's last).  A load thus has 8 to 10 quadrants, a good
+  // slab time, to arrive, and loads are issued in every quadrant but three.
+#define ENERGON_SLAB(kt_, cur, nxt)                                                                     \
   {                                                                                                     \
-    const int kl3 = (kt_) + 3 < KT ? (kt_) + 3 : klast;                                                 \
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 1, RN, 0, kl3, RN, 4, WN_);                                        \
-    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory"); /* LDS returns in order: the reads are back */  \
-    ENERGON_STEP(fa1, fb1, fa0, fb0, 2, RN, 4, kl3, RN, 8, WN_);                                        \
-    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
-    ENERGON_STEP(fa0, fb0, fa1, fb1, 3, RN, 8, kl3, RN, 12, WN_);                                       \
-    /* this wavefront has read all of the current buffer and written all of slab kt+1 */                \
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                                  \
-    __builtin_amdgcn_s_barrier();                                                                       \
-    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) { aaddr[ks] ^= 0x10000u; baddr[ks] ^= 0x10000u; }  \
-    ENERGON_STEP(fa1, fb1, fa0, fb0, 0, RN, 12, kl3, RC, 0, WC);                                        \
-    asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");                                                  \
+    const int kl2 = (kt_) + 2 < KT ? (kt_) + 2 : klast;                                                 \
+    ENERGON_QUAD(0, 0, ENERGON_RB(4, 0), ENERGON_RB(5, 0), ENERGON_RB(6, 0), ENERGON_RB(7, 0),           \
+                 ENERGON_NONE, ENERGON_NONE, ENERGON_NONE, ENERGON_NONE, ENERGON_SYNC(16));             \
+    ENERGON_QUAD(0, 4, ENERGON_RA(4, 0), ENERGON_RA(5, 0), ENERGON_RA(6, 0), ENERGON_RA(7, 0),           \
+                 ENERGON_NONE, ENERGON_NONE, ENERGON_NONE, ENERGON_NONE, ENERGON_READS_BACK);           \
+    ENERGON_QUAD(4, 4, ENERGON_RA(0, 1), ENERGON_RA(1, 1), ENERGON_RA(2, 1), ENERGON_RA(3, 1),           \
+                 ENERGON_NONE, ENERGON_NONE, ENERGON_NONE, ENERGON_NONE, ENERGON_SYNC(16));             \
+    ENERGON_QUAD(4, 0, ENERGON_RB(4, 1), ENERGON_RB(5, 1), ENERGON_RB(6, 1), ENERGON_RB(7, 1),           \
+                 ENERGON_DMA(0, 0, kl2, cur), ENERGON_DMA(0, 1, kl2, cur), ENERGON_NONE, ENERGON_NONE,   \
+                 ENERGON_SYNC(18));                                                                     \
+    ENERGON_QUAD(0, 4, ENERGON_RB(0, 1), ENERGON_RB(1, 1), ENERGON_RB(2, 1), ENERGON_RB(3, 1),           \
+                 ENERGON_DMA(0, 2, kl2, cur), ENERGON_DMA(0, 3, kl2, cur), ENERGON_DMA(1, 0, kl2, cur),  \
+                 ENERGON_DMA(1, 1, kl2, cur), ENERGON_SYNC(22));                                        \
+    ENERGON_QUAD(0, 0, ENERGON_RA(4, 1), ENERGON_RA(5, 1), ENERGON_RA(6, 1), ENERGON_RA(7, 1),           \
+                 ENERGON_DMA(1, 2, kl2, cur), ENERGON_DMA(1, 3, kl2, cur), ENERGON_DMA(2, 0, kl2, cur),  \
+                 ENERGON_DMA(2, 1, kl2, cur), ENERGON_SYNC(22));                                        \
+    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) { aaddr[ks] ^= 0x10000u; baddr[ks] ^= 0x10000u; }  \
+    ENERGON_QUAD(4, 0, ENERGON_RA(0, 0), ENERGON_RA(1, 0), ENERGON_RA(2, 0), ENERGON_RA(3, 0),           \
+                 ENERGON_DMA(2, 2, kl2, cur), ENERGON_DMA(2, 3, kl2, cur), ENERGON_DMA(3, 0, kl2, cur),  \
+                 ENERGON_DMA(3, 1, kl2, cur), ENERGON_SYNC(18));                                        \
+    ENERGON_QUAD(4, 4, ENERGON_RB(0, 0), ENERGON_RB(1, 0), ENERGON_RB(2, 0), ENERGON_RB(3, 0),           \
+                 ENERGON_DMA(3, 2, kl2, cur), ENERGON_DMA(3, 3, kl2, cur), ENERGON_NONE, ENERGON_NONE,   \
+                 ENERGON_READS_BACK);                                                                   \
   }
   for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0, checked by the launcher)
-    ENERGON_SLAB(rs0, rs1, wa0, wa1, kt)
-    ENERGON_SLAB(rs1, rs0, wa1, wa0, kt + 1)
+    ENERGON_SLAB(kt, 0, 1)
+    ENERGON_SLAB(kt + 1, 1, 0)
     // Last trip only: let the MFMA pipeline run empty before control leaves the loop.  Past this
     // point the compiler moves accumulators between registers as it pleases, and it knows of no
     // MFMA in flight (they are inside asm statements), so it would add none of the wait states
@@ -465,12 +467,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
                  : "scc", "memory");
   }
 #undef ENERGON_SLAB
-  // Outstanding loads (the clamped refetches of the last slabs) and LDS writes.
+  // Outstanding loads (the clamped refetches of the last slabs) still write to LDS.
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-#undef ENERGON_GLOAD
-#undef ENERGON_LWRITE
-#undef ENERGON_STEP
-#undef ENERGON_READ_SET
+#undef ENERGON_DMA
+#undef ENERGON_QUAD
+#undef ENERGON_SYNC
+#undef ENERGON_READS_BACK
+#undef ENERGON_NONE
+#undef ENERGON_RA
+#undef ENERGON_RB
+#undef ENERGON_MF
 
   // The epilogue's per-lane addresses must not be computed (and kept live) above the slab loop,
   // where every VGPR is spoken for: route the lane id through an ordered asm statement.
