@@ -383,7 +383,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
     __builtin_amdgcn_s_barrier();                                         \
   } while (0)
 
-// One quadrant: the 16 MFMAs of A tiles ai..ai+3 against B tiles bj..bj+3 with, slotted between
+// One quadrant: the 16 MFMAs of A tiles ai..ai+3 against B tiles bj..bj+3 (rows walked back and
+// forth, so that consecutive MFMAs share an operand: measurably less power) with, slotted between
 // them, four LDS reads R0..R3 (fragments of a half that the previous quadrants have released) and
 // up to four slab loads D0..D3; TAIL is the synchronisation that ends it (the reads are back on
 // leaving in any case).
@@ -391,10 +392,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
   do {                                                                                         \
     ENERGON_MF(ai + 0, bj + 0); R0; ENERGON_MF(ai + 0, bj + 1); R1;                             \
     ENERGON_MF(ai + 0, bj + 2); R2; ENERGON_MF(ai + 0, bj + 3); R3;                             \
-    ENERGON_MF(ai + 1, bj + 0); D0; ENERGON_MF(ai + 1, bj + 1); D1;                             \
-    ENERGON_MF(ai + 1, bj + 2); D2; ENERGON_MF(ai + 1, bj + 3); D3;                             \
+    ENERGON_MF(ai + 1, bj + 3); D0; ENERGON_MF(ai + 1, bj + 2); D1;                             \
+    ENERGON_MF(ai + 1, bj + 1); D2; ENERGON_MF(ai + 1, bj + 0); D3;                             \
     ENERGON_MF(ai + 2, bj + 0); ENERGON_MF(ai + 2, bj + 1); ENERGON_MF(ai + 2, bj + 2); ENERGON_MF(ai + 2, bj + 3); \
-    ENERGON_MF(ai + 3, bj + 0); ENERGON_MF(ai + 3, bj + 1); ENERGON_MF(ai + 3, bj + 2); ENERGON_MF(ai + 3, bj + 3); \
+    ENERGON_MF(ai + 3, bj + 3); ENERGON_MF(ai + 3, bj + 2); ENERGON_MF(ai + 3, bj + 1); ENERGON_MF(ai + 3, bj + 0); \
     TAIL;                                                                                      \
   } while (0)
 #define ENERGON_READS_BACK asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
