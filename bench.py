@@ -72,17 +72,24 @@ def main():
     cfg = hz.layer_config(H, w.n_heads, w.head_dim, F, w.dtype, w.ln_eps)
 
     def time_steps(run, lengths, steps, warmup):
+        # wall clock over exactly `steps` steps between two synchronisations; per-step durations from
+        # HIP events on the launch stream (for the median and the minimum)
         for _ in range(warmup):
             run.forward(x_dev, lengths, dev_layers)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
+        marks[0].record()
+        for i in range(steps):
             run.forward(x_dev, lengths, dev_layers)
+            marks[i + 1].record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps * 1e3
+        wall = (time.perf_counter() - t0) / steps * 1e3
+        per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+        return wall, per_step[len(per_step) // 2], per_step[0]
 
     run = hz.PackedRun(cfg, B, S, T)
-    ms_step = time_steps(run, lens, args.steps, args.warmup)
+    ms_step, ms_step_median, ms_step_min = time_steps(run, lens, args.steps, args.warmup)
     ms_layer = ms_step / L
     value = T / (ms_layer * 1e-3)
     gemm_flops_layer = T * (8.0 * H * A + 4.0 * H * F)
@@ -92,7 +99,8 @@ def main():
     attn_flops_layer = 2.0 * A * float(np.sum(lens.astype(np.float64) * (lens + 1)))
     flops_layer = gemm_flops_layer + attn_flops_layer
     tflops = flops_layer / (ms_layer * 1e-3) / 1e12
-    log(f"[bench] packed: {ms_step:.3f} ms/step, {value:,.0f} tokens/s/layer, {tflops:.1f} TFLOP/s")
+    log(f"[bench] packed: {ms_step:.3f} ms/step (median {ms_step_median:.3f}, min {ms_step_min:.3f}), "
+        f"{value:,.0f} tokens/s/layer, {tflops:.1f} TFLOP/s")
 
     # ---- per-stage durations (HIP events on the launch stream), same kernels, same buffers ----
     stage_ms = {k: 0.0 for k in E.STAGE_NAMES}
@@ -143,7 +151,7 @@ def main():
         del run
         torch.cuda.empty_cache()
         run_p = hz.PackedRun(cfg, B, S, B * S)
-        ms_pad = time_steps(run_p, full, max(2, args.steps // 2), min(args.warmup, 2))
+        ms_pad, _, _ = time_steps(run_p, full, max(2, args.steps // 2), min(args.warmup, 2))
         padded = {"ms_per_step": ms_pad, "value": T / (ms_pad / L * 1e-3), "rows": B * S,
                   "speedup_packed_over_padded": ms_pad / ms_step, "rows_ratio": B * S / T}
         log(f"[bench] padded: {ms_pad:.3f} ms/step -> packed is {ms_pad / ms_step:.2f}x faster "
@@ -177,7 +185,8 @@ def main():
     out = {
         "metric": "effective (non-pad) tokens/s per layer forward",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_step, "ms_per_step_median": ms_step_median, "ms_per_step_min": ms_step_min,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "layers": L, "hidden": H, "heads": w.n_heads, "head_dim": w.head_dim,
                    "ffn": F, "batch": B, "max_len": S, "valid_tokens": T, "valid_fraction": T / (B * S),
