@@ -28,8 +28,10 @@ Readings the paper leaves open, fixed here (the same ones the HIP path follows):
 
 Pins (tests/test_oracle_*.py): brute-force unbatched runs, padding invariance,
 hand-computed one-token/one-head values, position-0 closed form, uniform-attention
-closed form, identity block with zero output weights, and per-stage agreement with
-textbook library routines.  No function here is "parity unpinned".
+closed form, identity block with zero output weights, per-stage agreement with
+textbook library routines, and (for the paper's padded attention path) round trips,
+closed-form indices and agreement with the variable-length attention on valid tokens.
+No function here is "parity unpinned".
 """
 import numpy as np
 from scipy.special import erf as _erf
@@ -119,6 +121,68 @@ def masked_causal_attention(q, k, v, length, n_heads, head_dim):
             p = np.exp(s - s.max())
             p = p / p.sum()
             out[i, c0:c1] = p @ v[J, c0:c1]
+    return out
+
+
+# ------------------------------------------------- the paper's own attention path
+# Sec. 4.3 keeps the attention core padded: padding is rebuilt in front of it and removed
+# behind it, each fused with the head transpose ("two kernels that fuse the transpose and
+# pad operations").  These three functions are that path written out as plain index maps;
+# on valid tokens it must equal the variable-length attention above (tests pin that).
+def rebuild_qkv_heads(qkv_packed, lengths, S, n_heads, head_dim):
+    """[T, 3A] packed rows (Q | K | V, head-major inside each third) -> q, k, v, each
+    [B, nh, S, d]:  q[b, h, s, :] = qkv_packed[cu[b]+s, h*d:(h+1)*d] for s < len[b],
+    zeros at the pad positions (k, v likewise from the second and last third)."""
+    qkv_packed = np.asarray(qkv_packed, dtype=np.float64)
+    lengths = np.asarray(lengths, dtype=np.int64)
+    B, A = lengths.shape[0], n_heads * head_dim
+    out = np.zeros((3, B, n_heads, S, head_dim), dtype=np.float64)
+    t = 0
+    for b in range(B):
+        for s_ in range(int(lengths[b])):
+            row = qkv_packed[t]
+            for which in range(3):
+                for h in range(n_heads):
+                    c0 = which * A + h * head_dim
+                    out[which, b, h, s_, :] = row[c0:c0 + head_dim]
+            t += 1
+    return out[0], out[1], out[2]
+
+
+def padded_attention_heads(q, k, v, lengths):
+    """Attention of every (sequence, head) over all S positions of the padded layout
+    [B, nh, S, d], with the key set J(i) = { j : j <= i and j < len[b] } (causal and
+    key-padding mask); a query with no allowed key (len[b] = 0) gives a zero row."""
+    q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    B, nh, S, d = q.shape
+    out = np.zeros_like(q)
+    scale = 1.0 / np.sqrt(float(d))
+    j = np.arange(S)
+    for b in range(B):
+        for h in range(nh):
+            for i in range(S):
+                J = j[(j <= i) & (j < int(lengths[b]))]
+                if J.size == 0:
+                    continue
+                s_ = (k[b, h, J] @ q[b, h, i]) * scale
+                p_ = np.exp(s_ - s_.max())
+                out[b, h, i] = (p_ / p_.sum()) @ v[b, h, J]
+    return out
+
+
+def remove_padding_heads(o_pad, lengths):
+    """[B, nh, S, d] -> packed [T, A]:  out[cu[b]+s, h*d:(h+1)*d] = o_pad[b, h, s, :]
+    for s < len[b] (the inverse transpose, fused with the removal of padding)."""
+    o_pad = np.asarray(o_pad, dtype=np.float64)
+    B, nh, S, d = o_pad.shape
+    T = int(np.sum(lengths))
+    out = np.zeros((T, nh * d), dtype=np.float64)
+    t = 0
+    for b in range(B):
+        for s_ in range(int(lengths[b])):
+            for h in range(nh):
+                out[t, h * d:(h + 1) * d] = o_pad[b, h, s_, :]
+            t += 1
     return out
 
 
