@@ -9,6 +9,8 @@ the timed region.  Prints ONE JSON line:
              GEMMs of a layer / their launch durations, measured with HIP events recorded on
              the launch stream between the stages (energon_layer_forward_profiled)
   padded     the same library run with every position treated as valid (no elimination)
+  paper_attention_path  the layer with the attention stage done the paper's way (padded core
+             between a rebuild-padding and a remove-padding transpose kernel)
   cpu_baseline  the CPU oracle timed on a bounded sample of whole sequences, one layer
 """
 import argparse
@@ -38,6 +40,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
+    ap.add_argument("--no-paper-path", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -144,6 +147,31 @@ def main():
     log(f"[bench] stages (ms/layer): " + ", ".join(f"{k}={v:.3f}" for k, v in stage_ms.items()) +
         f"; pack={pack_ms:.3f} unpack={unpack_ms:.3f}; GEMMs {gemm_tflops:.1f} TFLOP/s")
 
+    # ---- the paper's own attention path (Sec. 4.3): rebuild padding + transpose, padded attention
+    # core, remove padding + transpose, in place of the variable-length attention; same other stages ----
+    paper_path = None
+    if w.dtype == wl.BF16 and not args.no_paper_path:
+        padws = torch.empty(E.energon_drce_workspace_bytes(cfg, B, S), dtype=torch.uint8, device="cuda")
+        acc = {k: 0.0 for k in E.STAGE_NAMES}
+        n_rep = max(1, min(args.steps, 5))
+        for _ in range(n_rep):
+            src, dst = run.x_packed, run.y_packed
+            for layer in dev_layers:
+                ms = E.energon_layer_forward_drce(cfg, layer.struct, src, dst, T, run.cu, lens, S, run.workspace,
+                                                  padws, timed=True)
+                for k, v in ms.items():
+                    acc[k] += v
+                src, dst = dst, src
+        acc = {k: v / (n_rep * L) for k, v in acc.items()}
+        paper_path = {"attention_stage_ms_per_layer": acc["attn"], "layer_ms": sum(acc.values()),
+                      "variable_length_attention_ms_per_layer": stage_ms["attn"],
+                      "variable_length_layer_ms": sum(stage_ms.values()),
+                      "what": "rebuild padding + head transpose, padded causal attention over all S positions, "
+                              "inverse transpose + remove padding"}
+        log(f"[bench] paper's attention path: {acc['attn']:.3f} ms/layer for the attention stage "
+            f"(variable-length: {stage_ms['attn']:.3f}); layer {sum(acc.values()):.3f} vs {sum(stage_ms.values()):.3f} ms")
+        del padws
+
     # ---- padded (no-elimination) path: same library, every position valid ----
     padded = None
     if not args.no_padded:
@@ -200,7 +228,7 @@ def main():
                      "flops_per_launch": gemm_flops_layer / 4},
         "stage_ms_per_layer": stage_ms, "stage_tflops": stage_tflops,
         "pack_ms": pack_ms, "unpack_ms": unpack_ms, "hbm": hbm,
-        "padded": padded, "cpu_baseline": cpu,
+        "padded": padded, "paper_attention_path": paper_path, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 

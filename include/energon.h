@@ -183,6 +183,50 @@ int energon_attention(const void* qkv_dev, void* out_dev, const int32_t* cu_seql
                       int64_t T, int32_t B, int32_t max_len, int32_t n_heads, int32_t head_dim,
                       int32_t dtype, void* stream);
 
+/* ---- the paper's own attention path (Sec. 4.3), kept as a measured comparison point ---------
+ * There the attention core stays padded: padding is rebuilt in front of it and removed behind
+ * it, each fused with the head transpose ("two kernels that fuse the transpose and pad
+ * operations").  bf16 only (ENERGON_ERR_UNSUPPORTED otherwise); head_dim 64 or 128. */
+
+/* Rebuild padding + head transpose.  qkv_packed_dev [T, 3A] (as energon_attention reads it) ->
+ * q_pad_dev, k_pad_dev, v_pad_dev, each [B, n_heads, S, head_dim]:
+ *   q_pad[b, h, s, :] = qkv_packed[cu[b]+s, h*d : (h+1)*d]  for s < len[b], exact zeros elsewhere
+ * (k, v from the second and last third).  Every output element is written exactly once.
+ * qkv_packed_dev may be NULL when T = 0. */
+int energon_rebuild_qkv(const void* qkv_packed_dev, const int32_t* cu_seqlens_dev, int64_t T, int32_t B,
+                        int32_t S, int32_t n_heads, int32_t head_dim, int32_t dtype, void* q_pad_dev,
+                        void* k_pad_dev, void* v_pad_dev, void* stream);
+
+/* Padded attention core on [B, n_heads, S, head_dim] operands: every one of the S queries of
+ * every sequence is computed; query i sees keys j with j <= i and j < len[b] (causal and
+ * key-padding mask); a sequence of length 0 gives zero rows.  out_pad_dev has the same layout. */
+int energon_attention_padded(const void* q_pad_dev, const void* k_pad_dev, const void* v_pad_dev,
+                             const int32_t* cu_seqlens_dev, int32_t B, int32_t S, int32_t n_heads,
+                             int32_t head_dim, int32_t dtype, void* out_pad_dev, void* stream);
+
+/* Inverse transpose + remove padding:  attn_packed[cu[b]+s, h*d : (h+1)*d] = out_pad[b, h, s, :]
+ * for s < len[b].  attn_packed_dev [T, A] (may be NULL when T = 0: nothing is written). */
+int energon_remove_attn_padding(const void* out_pad_dev, const int32_t* cu_seqlens_dev, int64_t T, int32_t B,
+                                int32_t S, int32_t n_heads, int32_t head_dim, int32_t dtype,
+                                void* attn_packed_dev, void* stream);
+
+/* Bytes of the extra buffer energon_layer_forward_drce needs: q, k, v and the attention output
+ * in the padded head-major layout, 4 * B * S * A elements.  0 if cfg is invalid. */
+size_t energon_drce_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B, int32_t S);
+
+/* energon_layer_forward with the attention stage done the paper's way: rebuild padding
+ * (+ transpose), padded attention over all S positions, remove padding (+ transpose).  Same
+ * arguments plus pad_workspace_dev (energon_drce_workspace_bytes(cfg, B, max_len) bytes,
+ * 256-byte aligned); max_len is the padded length S.  stage_ms_host may be NULL; otherwise
+ * the call waits for the stream and reports the stage times as
+ * energon_layer_forward_profiled does, the three kernels together as ENERGON_STAGE_ATTN. */
+int energon_layer_forward_drce(const EnergonLayerConfig* cfg, const EnergonLayerWeights* weights,
+                               const void* x_packed_dev, void* y_packed_dev, int64_t T,
+                               const int32_t* cu_seqlens_dev, const int32_t* lengths_host, int32_t B,
+                               int32_t max_len, void* workspace_dev, size_t workspace_bytes,
+                               void* pad_workspace_dev, size_t pad_workspace_bytes, void* stream,
+                               float* stage_ms_host);
+
 #ifdef __cplusplus
 }
 #endif

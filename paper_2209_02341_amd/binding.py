@@ -65,9 +65,16 @@ def lib() -> C.CDLL:
         l.energon_layernorm.argtypes = [vp, vp, vp, vp, i64, i32, C.c_float, i32, vp]
         l.energon_linear.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
         l.energon_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+        l.energon_rebuild_qkv.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+        l.energon_attention_padded.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+        l.energon_remove_attn_padding.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp]
+        l.energon_drce_workspace_bytes.restype = sz
+        l.energon_drce_workspace_bytes.argtypes = [pcfg, i32, i32]
+        l.energon_layer_forward_drce.argtypes = layer_args[:-1] + [vp, sz, vp, C.POINTER(C.c_float)]
         for name in ("energon_workspace_layout", "energon_pack", "energon_unpack", "energon_layer_forward",
                      "energon_layer_forward_profiled", "energon_layernorm", "energon_linear",
-                     "energon_attention"):
+                     "energon_attention", "energon_rebuild_qkv", "energon_attention_padded",
+                     "energon_remove_attn_padding", "energon_layer_forward_drce"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -190,3 +197,44 @@ def energon_attention(qkv, out, cu_seqlens, B: int, max_len: int, n_heads: int, 
     T = qkv.shape[0]
     _check(lib().energon_attention(_ptr(qkv), _ptr(out), _ptr(cu_seqlens), T, int(B), int(max_len), int(n_heads),
                                    int(head_dim), _dtype_code(qkv), _stream(stream)), "energon_attention")
+
+
+# ---- the paper's own attention path (rebuild padding + transpose, padded core, remove padding)
+def energon_rebuild_qkv(qkv_packed, cu_seqlens, B: int, S: int, n_heads: int, head_dim: int, q_pad, k_pad, v_pad,
+                        stream=None) -> None:
+    T = qkv_packed.shape[0]
+    _check(lib().energon_rebuild_qkv(_ptr(qkv_packed), _ptr(cu_seqlens), int(T), int(B), int(S), int(n_heads),
+                                     int(head_dim), _dtype_code(qkv_packed), _ptr(q_pad), _ptr(k_pad), _ptr(v_pad),
+                                     _stream(stream)), "energon_rebuild_qkv")
+
+
+def energon_attention_padded(q_pad, k_pad, v_pad, cu_seqlens, out_pad, stream=None) -> None:
+    B, nh, S, d = q_pad.shape
+    _check(lib().energon_attention_padded(_ptr(q_pad), _ptr(k_pad), _ptr(v_pad), _ptr(cu_seqlens), B, S, nh, d,
+                                          _dtype_code(q_pad), _ptr(out_pad), _stream(stream)),
+           "energon_attention_padded")
+
+
+def energon_remove_attn_padding(out_pad, cu_seqlens, attn_packed, stream=None) -> None:
+    B, nh, S, d = out_pad.shape
+    T = attn_packed.shape[0]
+    _check(lib().energon_remove_attn_padding(_ptr(out_pad), _ptr(cu_seqlens), int(T), B, S, nh, d,
+                                             _dtype_code(out_pad), _ptr(attn_packed), _stream(stream)),
+           "energon_remove_attn_padding")
+
+
+def energon_drce_workspace_bytes(cfg: LayerConfig, B: int, S: int) -> int:
+    return int(lib().energon_drce_workspace_bytes(C.byref(cfg), int(B), int(S)))
+
+
+def energon_layer_forward_drce(cfg: LayerConfig, weights: LayerWeights, x_packed, y_packed, T: int, cu_seqlens,
+                               lengths, max_len: int, workspace, pad_workspace, stream=None, timed=False):
+    """Returns the per-stage milliseconds (dict) if timed, else None."""
+    lens = _lengths(lengths)
+    ms = (C.c_float * len(STAGE_NAMES))() if timed else None
+    _check(lib().energon_layer_forward_drce(C.byref(cfg), C.byref(weights), _ptr(x_packed), _ptr(y_packed), int(T),
+                                            _ptr(cu_seqlens), _ptr(lens), len(lens), int(max_len), _ptr(workspace),
+                                            int(workspace.numel() * workspace.element_size()), _ptr(pad_workspace),
+                                            int(pad_workspace.numel() * pad_workspace.element_size()),
+                                            _stream(stream), ms), "energon_layer_forward_drce")
+    return dict(zip(STAGE_NAMES, (float(v) for v in ms))) if timed else None

@@ -36,11 +36,18 @@ template <int D> __device__ __forceinline__ int kswz(int row) {
 }
 __device__ __forceinline__ int vswz(int dd) { return (dd >> 1) & 7; }
 
-template <int D>
-__global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(const bf16_t* __restrict__ qkv,
-                                                                       bf16_t* __restrict__ out,
-                                                                       const int32_t* __restrict__ cu, int32_t nh,
-                                                                       int32_t n_qblocks, int32_t n_pairs) {
+// PADDED = false: Q, K, V are thirds of the packed [T, 3A] rows, the output is packed [T, A], and
+// only the len[b] real queries of a sequence are computed.  PADDED = true (the paper's own path,
+// Sec. 4.3): q, k, v, out are [B, nh, S, d] with zeros at the pads, all S queries are computed,
+// and a key is allowed iff it is <= the query and < len[b].
+template <int D, bool PADDED>
+__global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(const bf16_t* __restrict__ qptr,
+                                                                          const bf16_t* __restrict__ kptr,
+                                                                          const bf16_t* __restrict__ vptr,
+                                                                          bf16_t* __restrict__ out,
+                                                                          const int32_t* __restrict__ cu, int32_t nh,
+                                                                          int32_t n_qblocks, int32_t n_pairs,
+                                                                          int32_t S) {
   constexpr int KS = D / 32;        // 32-wide steps of the head dimension (S^T contraction)
   constexpr int DB = D / 16;        // 16-row blocks of O^T
   constexpr int KC = D / 8;         // 16-byte chunks per K row
@@ -60,20 +67,23 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
   const int32_t qb = n_qblocks - 1 - blockIdx.x / n_pairs;
   const int32_t c0 = cu[b], len = cu[b + 1] - c0;
   const int32_t q0 = qb * kBQ;
-  if (q0 >= len) return;  // whole workgroup leaves before any barrier
+  const int32_t n_queries = PADDED ? S : len;   // queries of this sequence that are computed
+  if (q0 >= n_queries) return;  // whole workgroup leaves before any barrier
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 15, g4 = lane >> 4;
   const int32_t A = nh * D;
-  const size_t ld = (size_t)3 * A;
-  const bf16_t* qbase = qkv + (size_t)c0 * ld + (size_t)h * D;
-  const bf16_t* kbase = qbase + A;
-  const bf16_t* vbase = qbase + 2 * (size_t)A;
+  // row stride and first row of this (sequence, head) in each operand
+  const size_t ld = PADDED ? (size_t)D : (size_t)3 * A;
+  const size_t first = PADDED ? (size_t)pair * S * D : (size_t)c0 * ld + (size_t)h * D;
+  const bf16_t* qbase = qptr + first;
+  const bf16_t* kbase = kptr + first;
+  const bf16_t* vbase = vptr + first;
 
   const int32_t wq_first = q0 + 16 * wave, wq_last = wq_first + 15;
   const int32_t qi = wq_first + lq;
-  const int32_t qc = qi < len ? qi : len - 1;
+  const int32_t qc = qi < n_queries ? qi : n_queries - 1;
 
   bf16x8 qf[KS];
 #pragma unroll
@@ -95,7 +105,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
   // the barrier that ended the previous trip), V into registers and from there, transposed, into
   // that buffer after the arithmetic.  The loop starts at t = -1 (fetch tile 0, nothing to
   // consume); past the end the last tile is fetched again and never used.
-  for (int32_t t = -1; t < n_tiles; ++t) {
+  for (int32_t t = n_tiles > 0 ? -1 : 0; t < n_tiles; ++t) {  // no tile at all: an empty sequence on the padded path
     const int32_t tn = t + 1 < n_tiles ? t + 1 : n_tiles - 1;
     uint4* ks_next = lds + ((t + 1) & 1) * kStage;
 #pragma unroll
@@ -127,8 +137,9 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
           sacc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[s], sacc[kb], 0, 0, 0);
         }
       }
-      // scale, causal mask (also hides keys >= len: they are > every valid query), tile max
-      const bool diag = k0 + kBKV - 1 > wq_first;
+      // scale, mask, tile max.  Packed: the causal mask also hides keys >= len (they are > every
+      // real query).  Padded: pad queries lie beyond len, so keys >= len are masked explicitly.
+      const bool diag = k0 + kBKV - 1 > wq_first || (PADDED && k0 + kBKV > len);
       float mx = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
@@ -137,7 +148,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
           float s = sacc[kb][e] * sc;
           if (diag) {
             const int32_t key = k0 + kb * 16 + g4 * 4 + e;
-            s = key > qi ? -INFINITY : s;
+            s = (key > qi || (PADDED && key >= len)) ? -INFINITY : s;
           }
           sacc[kb][e] = s;
           mx = fmaxf(mx, s);
@@ -204,9 +215,9 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
 
   float l_tot = l_run + __shfl_xor(l_run, 16, 64);
   l_tot += __shfl_xor(l_tot, 32, 64);
-  if (qi < len) {
-    const float inv = 1.0f / l_tot;
-    bf16_t* orow = out + (size_t)(c0 + qi) * A + (size_t)h * D;
+  if (qi < n_queries) {
+    const float inv = n_tiles > 0 ? 1.0f / l_tot : 0.f;   // no allowed key at all (len = 0): a zero row
+    bf16_t* orow = PADDED ? out + first + (size_t)qi * D : out + (size_t)(c0 + qi) * A + (size_t)h * D;
 #pragma unroll
     for (int i = 0; i < DB; ++i) {
       bf16x4 o4;
@@ -217,10 +228,10 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
   }
 }
 
-template <int D>
-static hipError_t launch_d(const bf16_t* qkv, bf16_t* out, const int32_t* cu, int32_t B, int32_t max_len, int32_t nh,
-                           hipStream_t s) {
-  auto kern = attention_bf16_kernel<D>;
+template <int D, bool PADDED>
+static hipError_t launch_d(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, const int32_t* cu, int32_t B,
+                           int32_t max_len, int32_t nh, hipStream_t s) {
+  auto kern = attention_bf16_kernel<D, PADDED>;
   constexpr size_t lds = 2 * (size_t)(kBKV * D * 2 + D * kBKV * 2);
   static bool attr_set = false;  // idempotent; a race between host threads only repeats the call
   if (!attr_set) {
@@ -232,14 +243,22 @@ static hipError_t launch_d(const bf16_t* qkv, bf16_t* out, const int32_t* cu, in
   const int32_t n_qblocks = (max_len + kBQ - 1) / kBQ;
   const int32_t n_pairs = B * nh;
   const int64_t grid = (int64_t)n_pairs * n_qblocks;
-  kern<<<dim3((unsigned)grid), dim3(kAttnWaves * 64), lds, s>>>(qkv, out, cu, nh, n_qblocks, n_pairs);
+  kern<<<dim3((unsigned)grid), dim3(kAttnWaves * 64), lds, s>>>(q, k, v, out, cu, nh, n_qblocks, n_pairs, max_len);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_bf16(const bf16_t* qkv, bf16_t* out, const int32_t* cu, int32_t B, int32_t max_len,
                                  int32_t nh, int32_t d, hipStream_t s) {
   if (B <= 0 || max_len <= 0) return hipSuccess;
-  return d == 128 ? launch_d<128>(qkv, out, cu, B, max_len, nh, s) : launch_d<64>(qkv, out, cu, B, max_len, nh, s);
+  const size_t A = (size_t)nh * d;
+  return d == 128 ? launch_d<128, false>(qkv, qkv + A, qkv + 2 * A, out, cu, B, max_len, nh, s)
+                  : launch_d<64, false>(qkv, qkv + A, qkv + 2 * A, out, cu, B, max_len, nh, s);
+}
+
+hipError_t launch_attention_padded_bf16(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out,
+                                        const int32_t* cu, int32_t B, int32_t S, int32_t nh, int32_t d, hipStream_t s) {
+  if (B <= 0 || S <= 0) return hipSuccess;
+  return d == 128 ? launch_d<128, true>(q, k, v, out, cu, B, S, nh, s) : launch_d<64, true>(q, k, v, out, cu, B, S, nh, s);
 }
 
 }  // namespace energon

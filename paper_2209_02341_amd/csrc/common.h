@@ -80,4 +80,12 @@ hipError_t launch_attention_f32(const float* qkv, float* out, const int32_t* cu,
 hipError_t launch_attention_bf16(const bf16_t* qkv, bf16_t* out, const int32_t* cu, int32_t B, int32_t max_len,
                                  int32_t nh, int32_t d, hipStream_t s);
 
+hipError_t launch_attention_padded_bf16(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out,
+                                        const int32_t* cu, int32_t B, int32_t S, int32_t nh, int32_t d, hipStream_t s);
+// drce.hip (head_bytes = bytes of one head's slice of a row: d * element size)
+hipError_t launch_rebuild_qkv(const void* qkv, void* q, void* k, void* v, const int32_t* cu, int32_t B, int32_t S,
+                              int32_t nh, int32_t head_bytes, hipStream_t s);
+hipError_t launch_remove_padding_heads(const void* o, void* out, const int32_t* cu, int32_t B, int32_t S, int32_t nh,
+                                       int32_t head_bytes, hipStream_t s);
+
 }  // namespace energon

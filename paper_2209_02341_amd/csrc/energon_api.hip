@@ -97,8 +97,11 @@ int check_layer_args(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w
 
 // The block itself.  ev == nullptr: plain launches; otherwise ev[0..STAGE_COUNT] are recorded
 // around the stages.
+// padws == nullptr: variable-length attention on the packed rows; otherwise the paper's path
+// (rebuild padding + transpose, padded attention, remove padding + transpose) through padws.
 int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y, int64_t T,
-               const int32_t* cu, int32_t B, int32_t max_len, void* ws, hipStream_t s, hipEvent_t* ev) {
+               const int32_t* cu, int32_t B, int32_t max_len, void* ws, hipStream_t s, hipEvent_t* ev,
+               void* padws = nullptr) {
   const WsLayout l = ws_layout(cfg, T);
   char* base = static_cast<char*>(ws);
   void* u = base + l.off[ENERGON_WS_U];
@@ -117,7 +120,17 @@ int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, cons
   MARK(1);
   STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, T, 3 * A, H, ENERGON_EPI_BIAS, dt, s));
   MARK(2);
-  if (T > 0) STEP(attention_impl(qkv, att, cu, B, max_len, cfg->n_heads, cfg->head_dim, dt, s));
+  if (T > 0 && padws == nullptr) {
+    STEP(attention_impl(qkv, att, cu, B, max_len, cfg->n_heads, cfg->head_dim, dt, s));
+  } else if (T > 0) {
+    const size_t part = (size_t)B * max_len * A * esize(dt);
+    char* pb = static_cast<char*>(padws);
+    const int32_t hb = cfg->head_dim * esize(dt);
+    HIP_TRY(launch_rebuild_qkv(qkv, pb, pb + part, pb + 2 * part, cu, B, max_len, cfg->n_heads, hb, s));
+    HIP_TRY(launch_attention_padded_bf16((const bf16_t*)pb, (const bf16_t*)(pb + part), (const bf16_t*)(pb + 2 * part),
+                                         (bf16_t*)(pb + 3 * part), cu, B, max_len, cfg->n_heads, cfg->head_dim, s));
+    HIP_TRY(launch_remove_padding_heads(pb + 3 * part, att, cu, B, max_len, cfg->n_heads, hb, s));
+  }
   MARK(3);
   STEP(linear_impl(att, w->w_o, w->b_o, x, y1, T, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
   MARK(4);
@@ -130,6 +143,27 @@ int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, cons
 #undef MARK
 #undef STEP
   return ENERGON_OK;
+}
+
+// layer_impl with a HIP event between the stages; waits for the stream.
+int layer_timed(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y, int64_t T,
+                const int32_t* cu, int32_t B, int32_t max_len, void* ws, hipStream_t s, void* padws, float* stage_ms) {
+  hipEvent_t ev[ENERGON_STAGE_COUNT + 1];
+  int made = 0;
+  for (; made <= ENERGON_STAGE_COUNT; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) break;
+  if (made <= ENERGON_STAGE_COUNT) {
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return ENERGON_ERR_HIP;
+  }
+  int st = layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, s, ev, padws);
+  if (st == ENERGON_OK && hipEventSynchronize(ev[ENERGON_STAGE_COUNT]) != hipSuccess) st = ENERGON_ERR_HIP;
+  if (st == ENERGON_OK)
+    for (int i = 0; i < ENERGON_STAGE_COUNT; ++i)
+      if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = ENERGON_ERR_HIP;
+  if (st != ENERGON_OK) (void)hipStreamSynchronize(s);
+  for (int i = 0; i <= ENERGON_STAGE_COUNT; ++i) (void)hipEventDestroy(ev[i]);
+  return st;
 }
 
 }  // namespace
@@ -212,25 +246,71 @@ int energon_layer_forward_profiled(const EnergonLayerConfig* cfg, const EnergonL
                                    void* y, int64_t T, const int32_t* cu, const int32_t* lengths, int32_t B,
                                    int32_t max_len, void* ws, size_t ws_bytes, void* stream, float* stage_ms) {
   if (!stage_ms) return ENERGON_ERR_NULL;
-  int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
+  const int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
   if (st != ENERGON_OK) return st;
+  return layer_timed(cfg, w, x, y, T, cu, B, max_len, ws, static_cast<hipStream_t>(stream), nullptr, stage_ms);
+}
+
+size_t energon_drce_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B, int32_t S) {
+  if (check_cfg(cfg) != ENERGON_OK || B <= 0 || S <= 0) return 0;
+  return (size_t)4 * B * S * cfg->n_heads * cfg->head_dim * esize(cfg->dtype);
+}
+
+static int check_drce_shape(const int32_t* cu, int64_t T, int32_t B, int32_t S, int32_t nh, int32_t d, int32_t dtype) {
+  if (!cu) return ENERGON_ERR_NULL;
+  if (dtype != ENERGON_BF16 || (d != 64 && d != 128)) return ENERGON_ERR_UNSUPPORTED;
+  if (B <= 0 || S <= 0 || nh <= 0 || T < 0 || T > (int64_t)B * S || (int64_t)B * S >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
+  if ((int64_t)B * nh >= (1 << 24)) return ENERGON_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(cu) & 3u) return ENERGON_ERR_ALIGN;
+  return ENERGON_OK;
+}
+
+int energon_rebuild_qkv(const void* qkv, const int32_t* cu, int64_t T, int32_t B, int32_t S, int32_t nh, int32_t d,
+                        int32_t dtype, void* q, void* k, void* v, void* stream) {
+  if ((!qkv && T > 0) || !q || !k || !v) return ENERGON_ERR_NULL;   // T = 0: no packed row is read
+  const int st = check_drce_shape(cu, T, B, S, nh, d, dtype);
+  if (st != ENERGON_OK) return st;
+  if (!aligned16(qkv) || !aligned16(q) || !aligned16(k) || !aligned16(v)) return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_rebuild_qkv(qkv, q, k, v, cu, B, S, nh, d * esize(dtype), static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_attention_padded(const void* q, const void* k, const void* v, const int32_t* cu, int32_t B, int32_t S,
+                             int32_t nh, int32_t d, int32_t dtype, void* out, void* stream) {
+  if (!q || !k || !v || !out) return ENERGON_ERR_NULL;
+  const int st = check_drce_shape(cu, 0, B, S, nh, d, dtype);
+  if (st != ENERGON_OK) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_attention_padded_bf16((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, cu, B, S, nh,
+                                       d, static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_remove_attn_padding(const void* o, const int32_t* cu, int64_t T, int32_t B, int32_t S, int32_t nh,
+                                int32_t d, int32_t dtype, void* out, void* stream) {
+  if (!o || (!out && T > 0)) return ENERGON_ERR_NULL;
+  const int st = check_drce_shape(cu, T, B, S, nh, d, dtype);
+  if (st != ENERGON_OK) return st;
+  if (!aligned16(o) || !aligned16(out)) return ENERGON_ERR_ALIGN;
+  if (T == 0) return ENERGON_OK;
+  HIP_TRY(launch_remove_padding_heads(o, out, cu, B, S, nh, d * esize(dtype), static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_layer_forward_drce(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y,
+                               int64_t T, const int32_t* cu, const int32_t* lengths, int32_t B, int32_t max_len,
+                               void* ws, size_t ws_bytes, void* padws, size_t padws_bytes, void* stream,
+                               float* stage_ms) {
+  const int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
+  if (st != ENERGON_OK) return st;
+  if (cfg->dtype != ENERGON_BF16) return ENERGON_ERR_UNSUPPORTED;
+  if (!padws) return ENERGON_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(padws) & 255u) != 0) return ENERGON_ERR_ALIGN;
+  if ((int64_t)B * max_len >= ((int64_t)1 << 31) || (int64_t)B * cfg->n_heads >= (1 << 24)) return ENERGON_ERR_SHAPE;
+  if (padws_bytes < energon_drce_workspace_bytes(cfg, B, max_len)) return ENERGON_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipEvent_t ev[ENERGON_STAGE_COUNT + 1];
-  int made = 0;
-  for (; made <= ENERGON_STAGE_COUNT; ++made)
-    if (hipEventCreate(&ev[made]) != hipSuccess) break;
-  if (made <= ENERGON_STAGE_COUNT) {
-    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
-    return ENERGON_ERR_HIP;
-  }
-  st = layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, s, ev);
-  if (st == ENERGON_OK && hipEventSynchronize(ev[ENERGON_STAGE_COUNT]) != hipSuccess) st = ENERGON_ERR_HIP;
-  if (st == ENERGON_OK)
-    for (int i = 0; i < ENERGON_STAGE_COUNT; ++i)
-      if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = ENERGON_ERR_HIP;
-  if (st != ENERGON_OK) (void)hipStreamSynchronize(s);
-  for (int i = 0; i <= ENERGON_STAGE_COUNT; ++i) (void)hipEventDestroy(ev[i]);
-  return st;
+  if (!stage_ms) return layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, s, nullptr, padws);
+  return layer_timed(cfg, w, x, y, T, cu, B, max_len, ws, s, padws, stage_ms);
 }
 
 int energon_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t T, int32_t H, float eps,

@@ -127,3 +127,26 @@ def test_stage_entry_points_reject_bad_arguments():
     assert l.energon_attention(FAKE, None, FAKE, 5, 2, 4, 2, 64, E.BF16, None) == -1
     assert l.energon_attention(FAKE, FAKE, FAKE, 5, 0, 4, 2, 64, E.BF16, None) == -2
     assert l.energon_attention(FAKE, FAKE, FAKE, 0, 2, 4, 2, 64, E.BF16, None) == 0   # T = 0: nothing to do
+
+
+def test_padded_attention_path_entry_points_reject_bad_arguments():
+    l = E.lib()
+    assert l.energon_rebuild_qkv(FAKE, FAKE, 5, 2, 4, 2, 64, E.BF16, FAKE, FAKE, None, None) == -1
+    assert l.energon_rebuild_qkv(FAKE, FAKE, 5, 2, 4, 2, 64, E.F32, FAKE, FAKE, FAKE, None) == -6
+    assert l.energon_rebuild_qkv(FAKE, FAKE, 5, 2, 4, 2, 96, E.BF16, FAKE, FAKE, FAKE, None) == -6
+    assert l.energon_rebuild_qkv(FAKE, FAKE, 9, 2, 4, 2, 64, E.BF16, FAKE, FAKE, FAKE, None) == -2   # T > B*S
+    assert l.energon_rebuild_qkv(FAKE, FAKE, 5, 2, 4, 2, 64, E.BF16, FAKE + 8, FAKE, FAKE, None) == -5
+    assert l.energon_attention_padded(FAKE, FAKE, FAKE, None, 2, 4, 2, 64, E.BF16, FAKE, None) == -1
+    assert l.energon_attention_padded(FAKE, FAKE, FAKE, FAKE, 2, 0, 2, 64, E.BF16, FAKE, None) == -2
+    assert l.energon_remove_attn_padding(FAKE, FAKE, 5, 2, 4, 2, 64, E.BF16, None, None) == -1
+    assert l.energon_remove_attn_padding(FAKE, FAKE, 0, 2, 4, 2, 64, E.BF16, FAKE, None) == 0   # T = 0: nothing to do
+    c = cfg()
+    assert E.energon_drce_workspace_bytes(c, 2, 4) == 4 * 2 * 4 * c.n_heads * c.head_dim * 2
+    assert E.energon_drce_workspace_bytes(c, 0, 4) == 0
+    w = E.LayerWeights(*([FAKE] * 12))
+    lens = np.asarray([3, 2], dtype=np.int32)
+    f = l.energon_layer_forward_drce
+    args = (C.byref(c), C.byref(w), FAKE, FAKE, 5, FAKE, lens.ctypes.data, 2, 4, FAKE, 1 << 30)
+    assert f(*args, None, 1 << 30, None, None) == -1
+    assert f(*args, FAKE, 16, None, None) == -4
+    assert f(*args, FAKE + 16, 1 << 30, None, None) == -5
