@@ -158,8 +158,11 @@ def test_linear_large_tile_kernel(K, epi):
     assert torch.equal(yd[:M].view(torch.int16), yd2[:M].view(torch.int16)), "not deterministic"
 
 
-def test_linear_residual_in_place():
-    dtype, M, N, K = wl.BF16, 130, 256, 128
+@pytest.mark.parametrize("M,N,K", [(130, 256, 128),       # small problem: the predicated kernel
+                                   (512, 24576, 128),     # 2 x 96 whole 256x256 tiles: the hand-scheduled kernel
+                                   (3333, 3592, 128)])    # ragged and large: shifted tiles would overlap, so predicated
+def test_linear_residual_in_place(M, N, K):
+    dtype = wl.BF16
     rng = np.random.default_rng(5)
     x = wl.round_to_dtype(rng.standard_normal((M, K)), dtype)
     w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
