@@ -24,7 +24,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA (fp16: the same)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # Bytes per GEMM launch at the L2 -> fabric boundary (mean of the four GEMMs of a layer), from the
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_gpt13b_bf16_hbm_traffic.md.
@@ -56,7 +56,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     w = wl.WORKLOADS[args.workload]
     L, H, A, F, B, S = w.layers, w.hidden, w.attn_width, w.ffn, w.batch, w.max_len
-    esz = 2 if w.dtype == wl.BF16 else 4
+    esz = 4 if w.dtype == wl.F32 else 2
     lens = wl.sample_lengths(w, args.seed)
     T = int(lens.sum())
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
@@ -150,7 +150,7 @@ def main():
     # ---- the paper's own attention path (Sec. 4.3): rebuild padding + transpose, padded attention
     # core, remove padding + transpose, in place of the variable-length attention; same other stages ----
     paper_path = None
-    if w.dtype == wl.BF16 and not args.no_paper_path:
+    if w.dtype != wl.F32 and not args.no_paper_path:
         padws = torch.empty(E.energon_drce_workspace_bytes(cfg, B, S), dtype=torch.uint8, device="cuda")
         acc = {k: 0.0 for k in E.STAGE_NAMES}
         n_rep = max(1, min(args.steps, 5))
@@ -220,7 +220,7 @@ def main():
                    "ffn": F, "batch": B, "max_len": S, "valid_tokens": T, "valid_fraction": T / (B * S),
                    "step": "pack + L x layer_forward + unpack"},
         "ms_per_layer": ms_layer, "tflops": tflops, "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops,
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_sched_kernel", "achieved": gemm_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES.get(w.name),
                      "algorithmic_bytes_per_launch": gemm_bytes_layer / 4,

@@ -20,7 +20,7 @@
  *   - Matrices are row-major and dense.  Weights are stored [out_features, in_features],
  *     so both GEMM operands are contiguous along the reduction.
  *   - Device pointers must be 16-byte aligned.  For a layer, H, A = n_heads*head_dim and F
- *     must be multiples of 64 (bf16) or 4 (fp32).
+ *     must be multiples of 64 (bf16, fp16) or 4 (fp32).
  *   - Sequences are right-padded: the valid tokens of sequence b are positions
  *     0 .. len[b]-1.  0 <= len[b] <= S.  len[b] = 0 and T = 0 are legal.
  *   - Packed order is batch-major then position: packed row cu[b] + s holds padded
@@ -49,7 +49,8 @@ typedef enum {
 
 typedef enum {
   ENERGON_F32 = 0,  /* fp32 storage, fp32 arithmetic (vector ALU)                        */
-  ENERGON_BF16 = 1  /* bf16 storage, MFMA with fp32 accumulation, fp32 epilogues         */
+  ENERGON_BF16 = 1, /* bf16 storage, MFMA with fp32 accumulation, fp32 epilogues         */
+  ENERGON_F16 = 2   /* fp16 storage (the paper's precision, Sec. 5.1), otherwise as bf16 */
 } energon_dtype;
 
 /* Geometry of ONE GPU's share of a layer.  For a tensor-parallel shard (Sec. 4.1.3) pass
@@ -169,7 +170,7 @@ int energon_layernorm(const void* x_dev, const void* gamma_dev, const void* beta
 
 /* y[M, N] = epilogue(x[M, K] W[N, K]^T + bias[N]) with residual r[M, N] for
  * ENERGON_EPI_BIAS_RESIDUAL (r may be the same buffer as y).  bias_dev may be NULL.
- * bf16: MFMA, fp32 accumulation, epilogue in fp32, one rounding to bf16 on store;
+ * bf16 / fp16: MFMA, fp32 accumulation, epilogue in fp32, one rounding on store;
  * needs K % 64 == 0 and N % 8 == 0.  fp32: N % 4 == 0, K % 4 == 0. */
 int energon_linear(const void* x_dev, const void* w_dev, const void* bias_dev,
                    const void* residual_dev, void* y_dev, int64_t M, int32_t N, int32_t K,
@@ -186,7 +187,7 @@ int energon_attention(const void* qkv_dev, void* out_dev, const int32_t* cu_seql
 /* ---- the paper's own attention path (Sec. 4.3), kept as a measured comparison point ---------
  * There the attention core stays padded: padding is rebuilt in front of it and removed behind
  * it, each fused with the head transpose ("two kernels that fuse the transpose and pad
- * operations").  bf16 only (ENERGON_ERR_UNSUPPORTED otherwise); head_dim 64 or 128. */
+ * operations").  bf16 and fp16 (ENERGON_ERR_UNSUPPORTED for fp32); head_dim 64 or 128. */
 
 /* Rebuild padding + head transpose.  qkv_packed_dev [T, 3A] (as energon_attention reads it) ->
  * q_pad_dev, k_pad_dev, v_pad_dev, each [B, n_heads, S, head_dim]:

@@ -14,7 +14,7 @@ import numpy as np
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libenergon.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL = 0, 1, 2
 WS_U, WS_QKV, WS_ATTN, WS_Y1, WS_W, WS_M, WS_COUNT = 0, 1, 2, 3, 4, 5, 6
 STAGE_NAMES = ("ln1", "qkv", "attn", "out", "ln2", "fc1", "fc2")
@@ -96,6 +96,8 @@ def _dtype_code(t) -> int:
     import torch
     if t.dtype == torch.bfloat16:
         return BF16
+    if t.dtype == torch.float16:
+        return F16
     if t.dtype == torch.float32:
         return F32
     raise TypeError(f"unsupported tensor dtype {t.dtype}")

@@ -1,4 +1,4 @@
-// bf16 causal attention over each sequence's real length, on packed rows.  The paper
+// Causal attention (bf16 or fp16 storage) over each sequence's real length, on packed rows.  The paper
 // (Sec. 4.3) rebuilds the padding around the attention core; here the core itself is
 // variable-length, so nothing is rebuilt inside a layer and no score is computed for a pad.
 //
@@ -9,7 +9,7 @@
 // eight wavefronts; tiles above the causal diagonal are never visited.
 //
 // Everything is computed transposed so that a query is a *column* of every MFMA result
-// (v_mfma_f32_16x16x32_bf16: the lane holds column lane % 16, rows 4 * (lane / 16) + e):
+// (v_mfma_f32_16x16x32_bf16 / _f16: the lane holds column lane % 16, rows 4 * (lane / 16) + e):
 //   S^T[key, query] = K[key, :] . Q[query, :]      A operand = K rows, B operand = Q rows
 //   O^T[dd,  query] += V^T[dd, key] . P^T[key, query]
 // so the online-softmax state (running max, running sum) is one scalar per lane, and the
@@ -40,11 +40,11 @@ __device__ __forceinline__ int vswz(int dd) { return (dd >> 1) & 7; }
 // only the len[b] real queries of a sequence are computed.  PADDED = true (the paper's own path,
 // Sec. 4.3): q, k, v, out are [B, nh, S, d] with zeros at the pads, all S queries are computed,
 // and a key is allowed iff it is <= the query and < len[b].
-template <int D, bool PADDED>
-__global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(const bf16_t* __restrict__ qptr,
-                                                                          const bf16_t* __restrict__ kptr,
-                                                                          const bf16_t* __restrict__ vptr,
-                                                                          bf16_t* __restrict__ out,
+template <typename E, int D, bool PADDED>
+__global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(const E* __restrict__ qptr,
+                                                                          const E* __restrict__ kptr,
+                                                                          const E* __restrict__ vptr,
+                                                                          E* __restrict__ out,
                                                                           const int32_t* __restrict__ cu, int32_t nh,
                                                                           int32_t n_qblocks, int32_t n_pairs,
                                                                           int32_t S) {
@@ -77,17 +77,17 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
   // row stride and first row of this (sequence, head) in each operand
   const size_t ld = PADDED ? (size_t)D : (size_t)3 * A;
   const size_t first = PADDED ? (size_t)pair * S * D : (size_t)c0 * ld + (size_t)h * D;
-  const bf16_t* qbase = qptr + first;
-  const bf16_t* kbase = kptr + first;
-  const bf16_t* vbase = vptr + first;
+  const E* qbase = qptr + first;
+  const E* kbase = kptr + first;
+  const E* vbase = vptr + first;
 
   const int32_t wq_first = q0 + 16 * wave, wq_last = wq_first + 15;
   const int32_t qi = wq_first + lq;
   const int32_t qc = qi < n_queries ? qi : n_queries - 1;
 
-  bf16x8 qf[KS];
+  vec8<E> qf[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)qc * ld + ks * 32 + 8 * g4);
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const vec8<E>*>(qbase + (size_t)qc * ld + ks * 32 + 8 * g4);
 
   const int32_t kv_end = min(q0 + kBQ, len);           // keys 0 .. kv_end-1 are needed
   const int32_t n_tiles = (kv_end + kBKV - 1) / kBKV;
@@ -133,8 +133,8 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
         const int row = kb * 16 + lq;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&ks[row * KC + ((s * 4 + g4) ^ kswz<D>(row))]);
-          sacc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[s], sacc[kb], 0, 0, 0);
+          const vec8<E> kf = *reinterpret_cast<const vec8<E>*>(&ks[row * KC + ((s * 4 + g4) ^ kswz<D>(row))]);
+          sacc[kb] = Mfma<E>::m16x16x32(kf, qf[s], sacc[kb]);
         }
       }
       // scale, mask, tile max.  Packed: the causal mask also hides keys >= len (they are > every
@@ -159,14 +159,14 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
       const bool rescale = __any(m_new != m_run);   // wavefront-uniform
       const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
       float psum = 0.f;
-      bf16x8 pf[2];
+      vec8<E> pf[2];
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float p = __builtin_amdgcn_exp2f(sacc[kb][e] - m_new);
           psum += p;
-          pf[kb >> 1][(kb & 1) * 4 + e] = static_cast<bf16_t>(p);
+          pf[kb >> 1][(kb & 1) * 4 + e] = static_cast<E>(p);
         }
       l_run = l_run * corr + psum;
       m_run = m_new;
@@ -185,9 +185,9 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
           const char* rowp = vt + dd * 128 + 8 * (g4 & 1);
           const uint2 lo = *reinterpret_cast<const uint2*>(rowp + (((4 * s + (g4 >> 1)) ^ vswz(dd)) * 16));
           const uint2 hi = *reinterpret_cast<const uint2*>(rowp + (((4 * s + 2 + (g4 >> 1)) ^ vswz(dd)) * 16));
-          union { uint4 u; bf16x8 v; } vf;
+          union { uint4 u; vec8<E> v; } vf;
           vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[s], oacc[i], 0, 0, 0);
+          oacc[i] = Mfma<E>::m16x16x32(vf.v, pf[s], oacc[i]);
         }
       }
     }
@@ -217,21 +217,21 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_bf16_kernel(cons
   l_tot += __shfl_xor(l_tot, 32, 64);
   if (qi < n_queries) {
     const float inv = n_tiles > 0 ? 1.0f / l_tot : 0.f;   // no allowed key at all (len = 0): a zero row
-    bf16_t* orow = PADDED ? out + first + (size_t)qi * D : out + (size_t)(c0 + qi) * A + (size_t)h * D;
+    E* orow = PADDED ? out + first + (size_t)qi * D : out + (size_t)(c0 + qi) * A + (size_t)h * D;
 #pragma unroll
     for (int i = 0; i < DB; ++i) {
-      bf16x4 o4;
+      vec4<E> o4;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o4[e] = static_cast<bf16_t>(oacc[i][e] * inv);
-      *reinterpret_cast<bf16x4*>(orow + i * 16 + g4 * 4) = o4;
+      for (int e = 0; e < 4; ++e) o4[e] = static_cast<E>(oacc[i][e] * inv);
+      *reinterpret_cast<vec4<E>*>(orow + i * 16 + g4 * 4) = o4;
     }
   }
 }
 
-template <int D, bool PADDED>
-static hipError_t launch_d(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, const int32_t* cu, int32_t B,
-                           int32_t max_len, int32_t nh, hipStream_t s) {
-  auto kern = attention_bf16_kernel<D, PADDED>;
+template <typename E, int D, bool PADDED>
+static hipError_t launch_d(const E* q, const E* k, const E* v, E* out, const int32_t* cu, int32_t B, int32_t max_len,
+                           int32_t nh, hipStream_t s) {
+  auto kern = attention_mfma_kernel<E, D, PADDED>;
   constexpr size_t lds = 2 * (size_t)(kBKV * D * 2 + D * kBKV * 2);
   static bool attr_set = false;  // idempotent; a race between host threads only repeats the call
   if (!attr_set) {
@@ -247,18 +247,38 @@ static hipError_t launch_d(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf
   return hipGetLastError();
 }
 
-hipError_t launch_attention_bf16(const bf16_t* qkv, bf16_t* out, const int32_t* cu, int32_t B, int32_t max_len,
-                                 int32_t nh, int32_t d, hipStream_t s) {
+template <typename E>
+static hipError_t launch_packed(const E* qkv, E* out, const int32_t* cu, int32_t B, int32_t max_len, int32_t nh,
+                                int32_t d, hipStream_t s) {
   if (B <= 0 || max_len <= 0) return hipSuccess;
   const size_t A = (size_t)nh * d;
-  return d == 128 ? launch_d<128, false>(qkv, qkv + A, qkv + 2 * A, out, cu, B, max_len, nh, s)
-                  : launch_d<64, false>(qkv, qkv + A, qkv + 2 * A, out, cu, B, max_len, nh, s);
+  return d == 128 ? launch_d<E, 128, false>(qkv, qkv + A, qkv + 2 * A, out, cu, B, max_len, nh, s)
+                  : launch_d<E, 64, false>(qkv, qkv + A, qkv + 2 * A, out, cu, B, max_len, nh, s);
 }
 
+template <typename E>
+static hipError_t launch_padded(const E* q, const E* k, const E* v, E* out, const int32_t* cu, int32_t B, int32_t S,
+                                int32_t nh, int32_t d, hipStream_t s) {
+  if (B <= 0 || S <= 0) return hipSuccess;
+  return d == 128 ? launch_d<E, 128, true>(q, k, v, out, cu, B, S, nh, s)
+                  : launch_d<E, 64, true>(q, k, v, out, cu, B, S, nh, s);
+}
+
+hipError_t launch_attention_bf16(const bf16_t* qkv, bf16_t* out, const int32_t* cu, int32_t B, int32_t max_len,
+                                 int32_t nh, int32_t d, hipStream_t s) {
+  return launch_packed<bf16_t>(qkv, out, cu, B, max_len, nh, d, s);
+}
+hipError_t launch_attention_f16(const f16_t* qkv, f16_t* out, const int32_t* cu, int32_t B, int32_t max_len, int32_t nh,
+                                int32_t d, hipStream_t s) {
+  return launch_packed<f16_t>(qkv, out, cu, B, max_len, nh, d, s);
+}
 hipError_t launch_attention_padded_bf16(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out,
                                         const int32_t* cu, int32_t B, int32_t S, int32_t nh, int32_t d, hipStream_t s) {
-  if (B <= 0 || S <= 0) return hipSuccess;
-  return d == 128 ? launch_d<128, true>(q, k, v, out, cu, B, S, nh, s) : launch_d<64, true>(q, k, v, out, cu, B, S, nh, s);
+  return launch_padded<bf16_t>(q, k, v, out, cu, B, S, nh, d, s);
+}
+hipError_t launch_attention_padded_f16(const f16_t* q, const f16_t* k, const f16_t* v, f16_t* out, const int32_t* cu,
+                                       int32_t B, int32_t S, int32_t nh, int32_t d, hipStream_t s) {
+  return launch_padded<f16_t>(q, k, v, out, cu, B, S, nh, d, s);
 }
 
 }  // namespace energon

@@ -7,8 +7,11 @@
 namespace energon {
 
 typedef __bf16 bf16_t;
+typedef _Float16 f16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+template <typename E> using vec8 = E __attribute__((ext_vector_type(8)));   // one MFMA operand fragment
+template <typename E> using vec4 = E __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -25,6 +28,31 @@ template <> struct Elem<bf16_t> {
   static constexpr int VEC = 8;
   __device__ static inline float to_f32(bf16_t v) { return static_cast<float>(v); }
   __device__ static inline bf16_t from_f32(float v) { return static_cast<bf16_t>(v); }  // RNE
+};
+
+template <> struct Elem<f16_t> {
+  static constexpr int VEC = 8;
+  __device__ static inline float to_f32(f16_t v) { return static_cast<float>(v); }
+  __device__ static inline f16_t from_f32(float v) { return static_cast<f16_t>(v); }  // RNE
+};
+
+// The two 16-bit MFMA forms of gfx950 for an element type (bf16 or fp16), fp32 accumulation.
+template <typename E> struct Mfma;
+template <> struct Mfma<bf16_t> {
+  __device__ static inline f32x16 m32x32x16(vec8<bf16_t> a, vec8<bf16_t> b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  __device__ static inline f32x4 m16x16x32(vec8<bf16_t> a, vec8<bf16_t> b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct Mfma<f16_t> {
+  __device__ static inline f32x16 m32x32x16(vec8<f16_t> a, vec8<f16_t> b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+  __device__ static inline f32x4 m16x16x32(vec8<f16_t> a, vec8<f16_t> b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
 };
 
 template <typename T> struct alignas(16) Vec16 { T v[Elem<T>::VEC]; };
@@ -67,21 +95,28 @@ hipError_t launch_pack_rows(const void* x_padded, void* x_packed, const int32_t*
 hipError_t launch_unpack_rows(const void* y_packed, void* y_padded, const int32_t* cu, int32_t B, int32_t S,
                               int64_t row_bytes, hipStream_t s);
 // layernorm.hip
+// dtype: 0 fp32, 1 bf16, 2 fp16 (the values of energon_dtype)
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t T, int32_t H,
-                            float eps, bool bf16, hipStream_t s);
-// gemm_f32.hip / gemm_bf16.hip
+                            float eps, int dtype, hipStream_t s);
+// gemm_f32.hip / gemm_mfma.hip (16-bit element types on the matrix cores)
 hipError_t launch_gemm_f32(const float* x, const float* w, const float* bias, const float* res, float* y,
                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
 hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
                             int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
-// attention_f32.hip / attention_bf16.hip
+hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y,
+                           int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
+// attention_f32.hip / attention_mfma.hip
 hipError_t launch_attention_f32(const float* qkv, float* out, const int32_t* cu, int32_t B, int32_t max_len,
                                 int32_t nh, int32_t d, hipStream_t s);
 hipError_t launch_attention_bf16(const bf16_t* qkv, bf16_t* out, const int32_t* cu, int32_t B, int32_t max_len,
                                  int32_t nh, int32_t d, hipStream_t s);
 
+hipError_t launch_attention_f16(const f16_t* qkv, f16_t* out, const int32_t* cu, int32_t B, int32_t max_len,
+                                int32_t nh, int32_t d, hipStream_t s);
 hipError_t launch_attention_padded_bf16(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out,
                                         const int32_t* cu, int32_t B, int32_t S, int32_t nh, int32_t d, hipStream_t s);
+hipError_t launch_attention_padded_f16(const f16_t* q, const f16_t* k, const f16_t* v, f16_t* out,
+                                       const int32_t* cu, int32_t B, int32_t S, int32_t nh, int32_t d, hipStream_t s);
 // drce.hip (head_bytes = bytes of one head's slice of a row: d * element size)
 hipError_t launch_rebuild_qkv(const void* qkv, void* q, void* k, void* v, const int32_t* cu, int32_t B, int32_t S,
                               int32_t nh, int32_t head_bytes, hipStream_t s);

@@ -8,9 +8,10 @@ using namespace energon;
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline int esize(int32_t dt) { return dt == ENERGON_BF16 ? 2 : 4; }
-inline int vec_elems(int32_t dt) { return dt == ENERGON_BF16 ? 8 : 4; }
-inline bool dtype_ok(int32_t dt) { return dt == ENERGON_F32 || dt == ENERGON_BF16; }
+inline bool is16(int32_t dt) { return dt == ENERGON_BF16 || dt == ENERGON_F16; }
+inline int esize(int32_t dt) { return is16(dt) ? 2 : 4; }
+inline int vec_elems(int32_t dt) { return is16(dt) ? 8 : 4; }
+inline bool dtype_ok(int32_t dt) { return dt == ENERGON_F32 || dt == ENERGON_BF16 || dt == ENERGON_F16; }
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ENERGON_ERR_HIP; } while (0)
 
@@ -21,8 +22,8 @@ int check_cfg(const EnergonLayerConfig* c) {
   if (c->head_dim != 64 && c->head_dim != 128) return ENERGON_ERR_UNSUPPORTED;
   const int64_t A = (int64_t)c->n_heads * c->head_dim;
   if (A > (1 << 28) || c->hidden > (1 << 28) || c->ffn > (1 << 28)) return ENERGON_ERR_SHAPE;
-  // bf16: every reduction dimension (H, A, F) is walked in 64-element slabs by the MFMA GEMM
-  const int div = c->dtype == ENERGON_BF16 ? 64 : 4;
+  // bf16 / fp16: every reduction dimension (H, A, F) is walked in 64-element slabs by the MFMA GEMM
+  const int div = is16(c->dtype) ? 64 : 4;
   if (c->hidden % div || A % div || c->ffn % div) return ENERGON_ERR_SHAPE;
   if (!(c->ln_eps >= 0.f)) return ENERGON_ERR_SHAPE;
   return ENERGON_OK;
@@ -57,6 +58,9 @@ int linear_impl(const void* x, const void* w, const void* bias, const void* res,
   if (dt == ENERGON_BF16)
     HIP_TRY(launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, (const bf16_t*)res, (bf16_t*)y,
                              M, N, K, epi, s));
+  else if (dt == ENERGON_F16)
+    HIP_TRY(launch_gemm_f16((const f16_t*)x, (const f16_t*)w, (const f16_t*)bias, (const f16_t*)res, (f16_t*)y, M, N,
+                            K, epi, s));
   else
     HIP_TRY(launch_gemm_f32((const float*)x, (const float*)w, (const float*)bias, (const float*)res, (float*)y, M, N,
                             K, epi, s));
@@ -67,8 +71,21 @@ int attention_impl(const void* qkv, void* out, const int32_t* cu, int32_t B, int
                    int32_t dt, hipStream_t s) {
   if (dt == ENERGON_BF16)
     HIP_TRY(launch_attention_bf16((const bf16_t*)qkv, (bf16_t*)out, cu, B, max_len, nh, d, s));
+  else if (dt == ENERGON_F16)
+    HIP_TRY(launch_attention_f16((const f16_t*)qkv, (f16_t*)out, cu, B, max_len, nh, d, s));
   else
     HIP_TRY(launch_attention_f32((const float*)qkv, (float*)out, cu, B, max_len, nh, d, s));
+  return ENERGON_OK;
+}
+
+int attention_padded_impl(const void* q, const void* k, const void* v, void* out, const int32_t* cu, int32_t B,
+                          int32_t S, int32_t nh, int32_t d, int32_t dt, hipStream_t s) {
+  if (dt == ENERGON_BF16)
+    HIP_TRY(launch_attention_padded_bf16((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, cu, B, S,
+                                         nh, d, s));
+  else
+    HIP_TRY(launch_attention_padded_f16((const f16_t*)q, (const f16_t*)k, (const f16_t*)v, (f16_t*)out, cu, B, S, nh,
+                                        d, s));
   return ENERGON_OK;
 }
 
@@ -111,12 +128,11 @@ int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, cons
   void* wn = base + l.off[ENERGON_WS_W];
   void* m = base + l.off[ENERGON_WS_M];
   const int32_t H = cfg->hidden, A = cfg->n_heads * cfg->head_dim, F = cfg->ffn, dt = cfg->dtype;
-  const bool bf = dt == ENERGON_BF16;
   int st;
 #define MARK(i) do { if (ev) HIP_TRY(hipEventRecord(ev[i], s)); } while (0)
 #define STEP(call) do { st = (call); if (st != ENERGON_OK) return st; } while (0)
   MARK(0);
-  HIP_TRY(launch_layernorm(x, w->ln1_g, w->ln1_b, u, T, H, cfg->ln_eps, bf, s));
+  HIP_TRY(launch_layernorm(x, w->ln1_g, w->ln1_b, u, T, H, cfg->ln_eps, dt, s));
   MARK(1);
   STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, T, 3 * A, H, ENERGON_EPI_BIAS, dt, s));
   MARK(2);
@@ -127,14 +143,14 @@ int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, cons
     char* pb = static_cast<char*>(padws);
     const int32_t hb = cfg->head_dim * esize(dt);
     HIP_TRY(launch_rebuild_qkv(qkv, pb, pb + part, pb + 2 * part, cu, B, max_len, cfg->n_heads, hb, s));
-    HIP_TRY(launch_attention_padded_bf16((const bf16_t*)pb, (const bf16_t*)(pb + part), (const bf16_t*)(pb + 2 * part),
-                                         (bf16_t*)(pb + 3 * part), cu, B, max_len, cfg->n_heads, cfg->head_dim, s));
+    STEP(attention_padded_impl(pb, pb + part, pb + 2 * part, pb + 3 * part, cu, B, max_len, cfg->n_heads,
+                               cfg->head_dim, dt, s));
     HIP_TRY(launch_remove_padding_heads(pb + 3 * part, att, cu, B, max_len, cfg->n_heads, hb, s));
   }
   MARK(3);
   STEP(linear_impl(att, w->w_o, w->b_o, x, y1, T, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
   MARK(4);
-  HIP_TRY(launch_layernorm(y1, w->ln2_g, w->ln2_b, wn, T, H, cfg->ln_eps, bf, s));
+  HIP_TRY(launch_layernorm(y1, w->ln2_g, w->ln2_b, wn, T, H, cfg->ln_eps, dt, s));
   MARK(5);
   STEP(linear_impl(wn, w->w_fc1, w->b_fc1, nullptr, m, T, F, H, ENERGON_EPI_BIAS_GELU, dt, s));
   MARK(6);
@@ -258,7 +274,7 @@ size_t energon_drce_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B, in
 
 static int check_drce_shape(const int32_t* cu, int64_t T, int32_t B, int32_t S, int32_t nh, int32_t d, int32_t dtype) {
   if (!cu) return ENERGON_ERR_NULL;
-  if (dtype != ENERGON_BF16 || (d != 64 && d != 128)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype) || (d != 64 && d != 128)) return ENERGON_ERR_UNSUPPORTED;
   if (B <= 0 || S <= 0 || nh <= 0 || T < 0 || T > (int64_t)B * S || (int64_t)B * S >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
   if ((int64_t)B * nh >= (1 << 24)) return ENERGON_ERR_UNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(cu) & 3u) return ENERGON_ERR_ALIGN;
@@ -281,9 +297,7 @@ int energon_attention_padded(const void* q, const void* k, const void* v, const 
   const int st = check_drce_shape(cu, 0, B, S, nh, d, dtype);
   if (st != ENERGON_OK) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return ENERGON_ERR_ALIGN;
-  HIP_TRY(launch_attention_padded_bf16((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, cu, B, S, nh,
-                                       d, static_cast<hipStream_t>(stream)));
-  return ENERGON_OK;
+  return attention_padded_impl(q, k, v, out, cu, B, S, nh, d, dtype, static_cast<hipStream_t>(stream));
 }
 
 int energon_remove_attn_padding(const void* o, const int32_t* cu, int64_t T, int32_t B, int32_t S, int32_t nh,
@@ -303,7 +317,7 @@ int energon_layer_forward_drce(const EnergonLayerConfig* cfg, const EnergonLayer
                                float* stage_ms) {
   const int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
   if (st != ENERGON_OK) return st;
-  if (cfg->dtype != ENERGON_BF16) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(cfg->dtype)) return ENERGON_ERR_UNSUPPORTED;
   if (!padws) return ENERGON_ERR_NULL;
   if ((reinterpret_cast<uintptr_t>(padws) & 255u) != 0) return ENERGON_ERR_ALIGN;
   if ((int64_t)B * max_len >= ((int64_t)1 << 31) || (int64_t)B * cfg->n_heads >= (1 << 24)) return ENERGON_ERR_SHAPE;
@@ -320,7 +334,7 @@ int energon_layernorm(const void* x, const void* gamma, const void* beta, void* 
   if (T < 0 || T >= ((int64_t)1 << 31) || H <= 0 || H % vec_elems(dtype) != 0 || !(eps >= 0.f)) return ENERGON_ERR_SHAPE;
   if (H / vec_elems(dtype) > 256 * 16) return ENERGON_ERR_UNSUPPORTED;
   if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y)) return ENERGON_ERR_ALIGN;
-  HIP_TRY(launch_layernorm(x, gamma, beta, y, T, H, eps, dtype == ENERGON_BF16, static_cast<hipStream_t>(stream)));
+  HIP_TRY(launch_layernorm(x, gamma, beta, y, T, H, eps, dtype, static_cast<hipStream_t>(stream)));
   return ENERGON_OK;
 }
 
@@ -331,7 +345,7 @@ int energon_linear(const void* x, const void* w, const void* bias, const void* r
   if (epilogue < ENERGON_EPI_BIAS || epilogue > ENERGON_EPI_BIAS_RESIDUAL) return ENERGON_ERR_UNSUPPORTED;
   if (epilogue == ENERGON_EPI_BIAS_RESIDUAL && !residual) return ENERGON_ERR_NULL;
   if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0) return ENERGON_ERR_SHAPE;
-  if (dtype == ENERGON_BF16 ? (K % 64 != 0 || N % 8 != 0) : (K % 4 != 0 || N % 4 != 0)) return ENERGON_ERR_SHAPE;
+  if (is16(dtype) ? (K % 64 != 0 || N % 8 != 0) : (K % 4 != 0 || N % 4 != 0)) return ENERGON_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(y))
     return ENERGON_ERR_ALIGN;
   return linear_impl(x, w, bias, residual, y, M, N, K, epilogue, dtype, static_cast<hipStream_t>(stream));

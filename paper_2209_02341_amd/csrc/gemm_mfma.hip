@@ -1,4 +1,4 @@
-// bf16 linear layer  y[M,N] = epilogue(x[M,K] W[N,K]^T + b)  on packed rows: the dense
+// 16-bit (bf16 or fp16) linear layer  y[M,N] = epilogue(x[M,K] W[N,K]^T + b)  on packed rows: the dense
 // contractions that the paper (Sec. 3.1, Sec. 5.5) reports as >95 % of a large layer's time
 // and that the padding removal (Sec. 4.3) shrinks from B*S rows to T rows.
 //
@@ -62,9 +62,9 @@ __device__ __forceinline__ bool tile_origin(int32_t tiles_m, int32_t tiles_n, in
 
 // Epilogue of one wavefront: TM x TN accumulator tiles of 32x32 whose top-left element is
 // (mw, nw).  In each tile the lane holds column (lane & 31), rows 8*(e/4) + 4*(lane/32) + e%4.
-template <int TM, int TN>
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const bf16_t* __restrict__ bias,
-                                           const bf16_t* res, bf16_t* y, int64_t M, int32_t N, int epi, int64_t mw,
+template <typename E, int TM, int TN>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const E* __restrict__ bias,
+                                           const E* res, E* y, int64_t M, int32_t N, int epi, int64_t mw,
                                            int32_t nw, int lane) {
   const int lrow = lane & 31, lhalf = lane >> 5;
 #pragma unroll
@@ -81,7 +81,7 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const bf
           float v = acc[i][j][e] + bv;
           if (epi == EPI_BIAS_GELU) v = gelu_erf(v);
           if (epi == EPI_BIAS_RESIDUAL) v += static_cast<float>(res[(size_t)m * N + n]);
-          y[(size_t)m * N + n] = static_cast<bf16_t>(v);
+          y[(size_t)m * N + n] = static_cast<E>(v);
         }
       }
     }
@@ -98,14 +98,15 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const bf
 // x / W slabs out of the L2 (measured: 1.4 % faster).
 constexpr int kEpiLd = 132;
 constexpr int kEpiWaveFloats = 64 * kEpiLd;
-__device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], const bf16_t* __restrict__ bias,
-                                                     const bf16_t* res, bf16_t* y, int32_t N, int epi, int64_t mw,
+template <typename E>
+__device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], const E* __restrict__ bias,
+                                                     const E* res, E* y, int32_t N, int epi, int64_t mw,
                                                      int32_t nw, int lane, float* stage) {
   const int lrow = lane & 15, lq = lane >> 4;
   const int rr = lane >> 4, c8 = (lane & 15) * 8;
   float bv[8];
   if (bias != nullptr) {
-    const bf16x8 b8 = *reinterpret_cast<const bf16x8*>(bias + nw + c8);
+    const vec8<E> b8 = *reinterpret_cast<const vec8<E>*>(bias + nw + c8);
 #pragma unroll
     for (int q = 0; q < 8; ++q) bv[q] = static_cast<float>(b8[q]);
   } else {
@@ -137,24 +138,24 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
         for (int q = 0; q < 8; ++q) v[q] = gelu_erf(v[q]);
       }
       if (epi == EPI_BIAS_RESIDUAL) {
-        const bf16x8 r8 = *reinterpret_cast<const bf16x8*>(res + off);
+        const vec8<E> r8 = *reinterpret_cast<const vec8<E>*>(res + off);
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] += static_cast<float>(r8[q]);
       }
-      bf16x8 o;
+      vec8<E> o;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) o[q] = static_cast<bf16_t>(v[q]);
-      __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(y + off));
+      for (int q = 0; q < 8; ++q) o[q] = static_cast<E>(v[q]);
+      __builtin_nontemporal_store(o, reinterpret_cast<vec8<E>*>(y + off));
     }
   }
 }
 
 // ---- compiler-scheduled tile kernel ---------------------------------------------------------
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_tile_kernel(const bf16_t* __restrict__ x,
-                                                                     const bf16_t* __restrict__ w,
-                                                                     const bf16_t* __restrict__ bias,
-                                                                     const bf16_t* res, bf16_t* y, int64_t M,
+template <typename E, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __restrict__ x,
+                                                                     const E* __restrict__ w,
+                                                                     const E* __restrict__ bias,
+                                                                     const E* res, E* y, int64_t M,
                                                                      int32_t N, int32_t K, int epi, int32_t tiles_m,
                                                                      int32_t tiles_n) {
   constexpr int NW = WM * WN;
@@ -230,26 +231,26 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_tile_kernel(const bf16_
   for (int kt = 0; kt < KT; ++kt) {
     const uint4* cur = smem + (kt & 1) * kStage;
     if (kt + 1 < KT) issue(kt + 1, (kt + 1) & 1);
-    bf16x8 af[2][TM], bfr[2][TN];
+    vec8<E> af[2][TM], bfr[2][TN];
 #pragma unroll
-    for (int t = 0; t < TM; ++t) af[0][t] = *reinterpret_cast<const bf16x8*>(&cur[fa[t] + (lhalf ^ fsa[t])]);
+    for (int t = 0; t < TM; ++t) af[0][t] = *reinterpret_cast<const vec8<E>*>(&cur[fa[t] + (lhalf ^ fsa[t])]);
 #pragma unroll
-    for (int t = 0; t < TN; ++t) bfr[0][t] = *reinterpret_cast<const bf16x8*>(&cur[fb[t] + (lhalf ^ fsb[t])]);
+    for (int t = 0; t < TN; ++t) bfr[0][t] = *reinterpret_cast<const vec8<E>*>(&cur[fb[t] + (lhalf ^ fsb[t])]);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       const int p = ks & 1;
       if (ks + 1 < BK / 16) {
         const int c = (ks + 1) * 2 + lhalf;
 #pragma unroll
-        for (int t = 0; t < TM; ++t) af[p ^ 1][t] = *reinterpret_cast<const bf16x8*>(&cur[fa[t] + (c ^ fsa[t])]);
+        for (int t = 0; t < TM; ++t) af[p ^ 1][t] = *reinterpret_cast<const vec8<E>*>(&cur[fa[t] + (c ^ fsa[t])]);
 #pragma unroll
-        for (int t = 0; t < TN; ++t) bfr[p ^ 1][t] = *reinterpret_cast<const bf16x8*>(&cur[fb[t] + (c ^ fsb[t])]);
+        for (int t = 0; t < TN; ++t) bfr[p ^ 1][t] = *reinterpret_cast<const vec8<E>*>(&cur[fb[t] + (c ^ fsb[t])]);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[p][i], bfr[p][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = Mfma<E>::m32x32x16(af[p][i], bfr[p][j], acc[i][j]);
       // issue order: one LDS read of the next step's operands after every two MFMAs of this step
       if (ks + 1 < BK / 16) {
 #pragma unroll
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_tile_kernel(const bf16_
     __syncthreads();
   }
 
-  store_tile<TM, TN>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane);
+  store_tile<E, TM, TN>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane);
 }
 
 // ---- hand-scheduled 256x256 kernel ----------------------------------------------------------
@@ -285,14 +286,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_tile_kernel(const bf16_
 // between a register write and an MFMA reading it (accumulator zeroing).
 #define ENERGON_DS_READ(dst, addr, off) \
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(off) : "memory")
-#define ENERGON_MFMA(acc, a, b) \
-  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b))
+#define ENERGON_MFMA(acc, a, b)                                                                          \
+  do {                                                                                                   \
+    if constexpr (__is_same(E, bf16_t))                                                                  \
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));              \
+    else                                                                                                 \
+      asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));               \
+  } while (0)
 
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16_t* __restrict__ x,
-                                                                    const bf16_t* __restrict__ w,
-                                                                    const bf16_t* __restrict__ bias,
-                                                                    const bf16_t* res, bf16_t* y, int64_t M,
+template <typename E, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* __restrict__ x,
+                                                                    const E* __restrict__ w,
+                                                                    const E* __restrict__ bias,
+                                                                    const E* res, E* y, int64_t M,
                                                                     int32_t N, int32_t K, int epi, int32_t tiles_m,
                                                                     int32_t tiles_n) {
   constexpr int NW = WM * WN;
@@ -371,7 +377,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
   __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[c][j] + (size_t)(kt_) * (BK * 2) + voff),              \
                                    (lptr_t)(reinterpret_cast<char*>(smem) + (buf) * 0x10000 + ldst[c][j]), 16, 0, 0)
 
-  bf16x8 fa[TM], fb[TN];  // the operand fragments: x-row tiles, W-row tiles
+  vec8<E> fa[TM], fb[TN];  // the operand fragments: x-row tiles, W-row tiles
 #define ENERGON_RA(t, ks) ENERGON_DS_READ(fa[t], aaddr[ks], (t) * 2048)
 #define ENERGON_RB(t, ks) ENERGON_DS_READ(fb[t], baddr[ks], (t) * 2048)
 #define ENERGON_MF(i, j) ENERGON_MFMA(acc[i][j], fa[i], fb[j])
@@ -490,9 +496,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_sched_kernel(const bf16
   ENERGON_STAMP(3);
 }
 
-template <typename Kern>
-static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int threads, size_t lds, const bf16_t* x,
-                               const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y, int64_t M, int32_t N,
+template <typename E, typename Kern>
+static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int threads, size_t lds, const E* x,
+                               const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
                                int32_t K, int epi, hipStream_t s) {
   if (!attr_set) {  // idempotent; a race between host threads only repeats the call
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -507,10 +513,11 @@ static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int th
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
-                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s) {
+template <typename E>
+static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
+                                   int32_t K, int epi, hipStream_t s) {
   if (M <= 0) return hipSuccess;
-  static bool attr_big = false, attr_small = false;
+  static bool attr_big = false, attr_small = false;  // per element type
   const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
   // the 256x256 kernel needs whole tiles to shift at the edges, an even number of slabs, and
   // enough tiles for most of the 256 CUs
@@ -520,11 +527,21 @@ hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias
   if (M >= 256 && N >= 256 && K % 128 == 0 && big_tiles >= 192 && overlap_safe) {
     constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
     constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
-    return launch_tiles(gemm_bf16_sched_kernel<256, 256, 2, 2>, attr_big, 256, 256, 256,
-                        slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, s);
+    return launch_tiles<E>(gemm_mfma_sched_kernel<E, 256, 256, 2, 2>, attr_big, 256, 256, 256,
+                           slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, s);
   }
-  return launch_tiles(gemm_bf16_tile_kernel<128, 128, 2, 2>, attr_small, 128, 128, 256,
-                      2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, s);
+  return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2>, attr_small, 128, 128, 256,
+                         2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, s);
+}
+
+hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
+                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s) {
+  return launch_gemm_mfma<bf16_t>(x, w, bias, res, y, M, N, K, epi, s);
+}
+
+hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y, int64_t M,
+                           int32_t N, int32_t K, int epi, hipStream_t s) {
+  return launch_gemm_mfma<f16_t>(x, w, bias, res, y, M, N, K, epi, s);
 }
 
 }  // namespace energon

@@ -96,9 +96,11 @@ static hipError_t dispatch(const void* x, const void* g, const void* b, void* y,
 
 // Largest H one launch handles (16 vectors of 8 or 4 elements in each of 256 threads).
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t T, int32_t H,
-                            float eps, bool bf16, hipStream_t s) {
+                            float eps, int dtype, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  return bf16 ? dispatch<bf16_t>(x, gamma, beta, y, T, H, eps, s) : dispatch<float>(x, gamma, beta, y, T, H, eps, s);
+  return dtype == 1 ? dispatch<bf16_t>(x, gamma, beta, y, T, H, eps, s)
+       : dtype == 2 ? dispatch<f16_t>(x, gamma, beta, y, T, H, eps, s)
+                    : dispatch<float>(x, gamma, beta, y, T, H, eps, s);
 }
 
 }  // namespace energon

@@ -18,6 +18,8 @@ def to_device(a: np.ndarray | None, dtype: str, device="cuda"):
     if dtype == wl.BF16:
         bits = wl.f32_to_bf16_bits(a)
         return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    if dtype == wl.F16:
+        return torch.from_numpy(a.astype(np.float16)).to(device)
     return torch.from_numpy(a).to(device)
 
 
@@ -27,7 +29,8 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 
 def layer_config(hidden, n_heads, head_dim, ffn, dtype: str, eps=1e-5) -> E.LayerConfig:
-    return E.LayerConfig(hidden, n_heads, head_dim, ffn, eps, E.BF16 if dtype == wl.BF16 else E.F32)
+    code = {wl.BF16: E.BF16, wl.F16: E.F16, wl.F32: E.F32}[dtype]
+    return E.LayerConfig(hidden, n_heads, head_dim, ffn, eps, code)
 
 
 class DeviceLayer:
@@ -42,7 +45,7 @@ class PackedRun:
     """Buffers for one batch: packed activations (ping/pong), cu_seqlens, token_idx, workspace."""
 
     def __init__(self, cfg: E.LayerConfig, B: int, S: int, capacity_tokens: int, device="cuda"):
-        tdt = torch.bfloat16 if cfg.dtype == E.BF16 else torch.float32
+        tdt = {E.BF16: torch.bfloat16, E.F16: torch.float16, E.F32: torch.float32}[cfg.dtype]
         cap = max(int(capacity_tokens), 1)
         self.cfg, self.B, self.S = cfg, B, S
         self.x_packed = torch.empty((cap, cfg.hidden), dtype=tdt, device=device)

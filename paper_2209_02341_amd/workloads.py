@@ -24,6 +24,7 @@ import numpy as np
 
 F32 = "f32"
 BF16 = "bf16"
+F16 = "f16"     # the paper's precision (Sec. 5.1)
 
 
 @dataclass(frozen=True)
@@ -56,6 +57,8 @@ WORKLOADS = {
     for w in [
         Workload("tiny_f32", F32, 1, 256, 4, 64, 1024, 4, 32, "uniform", 1, 32),
         Workload("small_bf16", BF16, 1, 1024, 16, 64, 4096, 8, 128, "uniform", 16, 128),
+        Workload("small_f16", F16, 1, 1024, 16, 64, 4096, 8, 128, "uniform", 16, 128),
+        Workload("gpt13b_f16", F16, 4, 5120, 40, 128, 20480, 32, 512, "uniform", 32, 512),
         Workload("gpt13b_bf16", BF16, 4, 5120, 40, 128, 20480, 32, 512, "uniform", 32, 512),
         Workload("gpt175b_tp8_shard_bf16", BF16, 1, 12288, 12, 128, 6144, 16, 1024,
                  "lognormal", 8, 1024, len_median=200.0, row_split_bias=False),
@@ -88,6 +91,8 @@ def round_to_dtype(a: np.ndarray, dtype: str) -> np.ndarray:
     a = np.ascontiguousarray(a, dtype=np.float32)
     if dtype == F32:
         return a
+    if dtype == F16:
+        return a.astype(np.float16).astype(np.float32)   # round to nearest even
     return bf16_bits_to_f32(f32_to_bf16_bits(a))
 
 
