@@ -142,7 +142,7 @@ int energon_unpack(const void* y_packed_dev, const int32_t* cu_seqlens_dev, int6
  *   cu_seqlens_dev [B+1] in; lengths_host [B] in (host; used for validation and launch
  *   shapes only: sum must equal T, each 0 <= len <= max_len);
  *   workspace_dev: at least energon_workspace_bytes(cfg, T) bytes, 256-byte aligned.
- * Errors: NULL, SHAPE (dims <= 0, H/A/F not multiples of 4 (bf16: of 64)),
+ * Errors: NULL, SHAPE (dims <= 0, H/A/F not multiples of 4 (bf16, fp16: of 64)),
  * LENGTH, CAPACITY (workspace), ALIGN, UNSUPPORTED (head_dim not 64/128, dtype), HIP. */
 int energon_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* weights,
                           const void* x_packed_dev, void* y_packed_dev, int64_t T,
