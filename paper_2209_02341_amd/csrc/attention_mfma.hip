@@ -95,11 +95,32 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
   f32x4 oacc[DB];
 #pragma unroll
   for (int i = 0; i < DB; ++i) oacc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
-  const float sc = rsqrtf((float)D) * kLog2e;  // scores are kept in log2 units
+  float m_run = -INFINITY, l_run = 0.f;        // running max in log2 units (already scaled), running sum
+  const float sc = rsqrtf((float)D) * kLog2e;  // raw score -> log2 units
 
+  // Addresses inside this (sequence, head): a wavefront-uniform base plus a 32-bit byte offset
+  // (the launcher checks that S rows fit in 32 bits).
+  const char* kbytes = reinterpret_cast<const char*>(kbase);
+  const char* vbytes = reinterpret_cast<const char*>(vbase);
+  const uint32_t ld_b = (uint32_t)(ld * sizeof(E));
   // this lane's part of a K tile transfer: row kr of the instruction's KROWS rows, LDS slot ksl
   const int kr = lane / KC, ksl = lane % KC;
+  uint32_t kcol[KDMA];   // byte offset of the chunk this lane fetches, inside its row
+#pragma unroll
+  for (int i = 0; i < KDMA; ++i) kcol[i] = (uint32_t)((ksl ^ kswz<D>((wave * KDMA + i) * KROWS + kr)) * 16);
+  // V transposition (see below): the lane holds 8 consecutive dd of key `lane` of the tile; with
+  // its neighbour (key ^ 1) it forms, per dd, the 32-bit word (even key, odd key).  Even lanes
+  // write dd 0, 2, 4, 6 of the chunk, odd lanes dd 1, 3, 5, 7.  One byte permute builds the word.
+  const int kp = lane >> 1, odd = lane & 1;
+  const uint32_t vsel = odd ? 0x03020706u : 0x05040100u;   // v_perm_b32 selector, bytes of {partner, own}
+  uint32_t vdst[VLOADS][4];  // word index of the store inside the V^T tile
+#pragma unroll
+  for (int j = 0; j < VLOADS; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int dd = (wave + kAttnWaves * j) * 8 + 2 * e + odd;
+      vdst[j][e] = (uint32_t)(dd * 32 + (((kp >> 2) ^ vswz(dd)) * 4) + (kp & 3));
+    }
 
   // Tile t+1 is fetched while tile t is consumed: K straight into the other LDS buffer (free since
   // the barrier that ended the previous trip), V into registers and from there, transposed, into
@@ -110,17 +131,17 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
     uint4* ks_next = lds + ((t + 1) & 1) * kStage;
 #pragma unroll
     for (int i = 0; i < KDMA; ++i) {
-      const int row = (wave * KDMA + i) * KROWS + kr;
-      int32_t key = tn * kBKV + row; key = key < len ? key : len - 1;
-      __builtin_amdgcn_global_load_lds((attn_gptr_t)(kbase + (size_t)key * ld + ((ksl ^ kswz<D>(row)) * 8)),
+      int32_t key = tn * kBKV + (wave * KDMA + i) * KROWS + kr; key = key < len ? key : len - 1;
+      __builtin_amdgcn_global_load_lds((attn_gptr_t)(kbytes + ((uint32_t)key * ld_b + kcol[i])),
                                        (attn_lptr_t)(ks_next + (wave * KDMA + i) * 64), 16, 0, 0);
     }
     uint4 vreg[VLOADS];
     {
       int32_t vkey = tn * kBKV + lane; vkey = vkey < len ? vkey : len - 1;
+      const uint32_t voff = (uint32_t)vkey * ld_b + (uint32_t)wave * 16u;
 #pragma unroll
       for (int j = 0; j < VLOADS; ++j)
-        vreg[j] = *reinterpret_cast<const uint4*>(vbase + (size_t)vkey * ld + (wave + kAttnWaves * j) * 8);
+        vreg[j] = *reinterpret_cast<const uint4*>(vbytes + (voff + (uint32_t)(kAttnWaves * j) * 16u));
     }
     const int32_t k0 = t * kBKV;
     if (t >= 0 && k0 <= wq_last) {  // wavefront-uniform: the tile is not wholly above this wavefront's diagonal
@@ -137,26 +158,35 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
           sacc[kb] = Mfma<E>::m16x16x32(kf, qf[s], sacc[kb]);
         }
       }
-      // scale, mask, tile max.  Packed: the causal mask also hides keys >= len (they are > every
-      // real query).  Padded: pad queries lie beyond len, so keys >= len are masked explicitly.
-      const bool diag = k0 + kBKV - 1 > wq_first || (PADDED && k0 + kBKV > len);
-      float mx = -INFINITY;
+      // Mask (only on tiles that touch the diagonal or, on the padded path, the end of the
+      // sequence: wavefront-uniform), then the tile max of the raw scores.  Packed: the causal
+      // mask also hides keys >= len (they are > every real query).  Padded: pad queries lie beyond
+      // len, so keys >= len are masked explicitly.
+      if (k0 + kBKV - 1 > wq_first || (PADDED && k0 + kBKV > len)) {
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb)
+        for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float s = sacc[kb][e] * sc;
-          if (diag) {
+          for (int e = 0; e < 4; ++e) {
             const int32_t key = k0 + kb * 16 + g4 * 4 + e;
-            s = (key > qi || (PADDED && key >= len)) ? -INFINITY : s;
+            if (key > qi || (PADDED && key >= len)) sacc[kb][e] = -INFINITY;
           }
-          sacc[kb][e] = s;
-          mx = fmaxf(mx, s);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);   // finite from tile 0 on: key 0 <= every query
-      const bool rescale = __any(m_new != m_run);   // wavefront-uniform
+      }
+      float mx = fmaxf(fmaxf(sacc[0][0], sacc[0][1]), fmaxf(sacc[0][2], sacc[0][3]));
+#pragma unroll
+      for (int kb = 1; kb < 4; ++kb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, sacc[kb][e]);
+      // the query's max over the four lane groups that hold its keys: exchange with lane ^ 16, then
+      // lane ^ 32 (v_permlane16_swap / v_permlane32_swap of a value with itself leave own and
+      // partner's value in the two results)
+      {
+        const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+        const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+      }
+      const float m_new = fmaxf(m_run, mx * sc);   // finite from tile 0 on: key 0 <= every query (sc > 0)
+      const bool rescale = __any(m_new != m_run);  // wavefront-uniform
       const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
       float psum = 0.f;
       vec8<E> pf[2];
@@ -164,7 +194,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float p = __builtin_amdgcn_exp2f(sacc[kb][e] - m_new);
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], sc, -m_new));
           psum += p;
           pf[kb >> 1][(kb & 1) * 4 + e] = static_cast<E>(p);
         }
@@ -193,19 +223,14 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
     }
     {
       uint32_t* vt = reinterpret_cast<uint32_t*>(ks_next + kBKV * KC);
-      // transpose: this lane holds 8 consecutive dd of one key; with its neighbour (key ^ 1) it
-      // forms, per dd, the 32-bit word (even key, odd key).  Even lanes write dd 0,2,4,6 of the
-      // chunk, odd lanes dd 1,3,5,7.
-      const int kp = lane >> 1, odd = lane & 1;
 #pragma unroll
       for (int j = 0; j < VLOADS; ++j) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const uint32_t we = e == 0 ? vreg[j].x : e == 1 ? vreg[j].y : e == 2 ? vreg[j].z : vreg[j].w;
-          const uint32_t p = (uint32_t)__shfl_xor((int)we, 1, 64);
-          const uint32_t word = odd ? ((p >> 16) | (we & 0xFFFF0000u)) : ((we & 0xFFFFu) | (p << 16));
-          const int dd = (wave + kAttnWaves * j) * 8 + 2 * e + odd;
-          vt[dd * 32 + (((kp >> 2) ^ vswz(dd)) * 4) + (kp & 3)] = word;
+          // the neighbour lane's word (lane ^ 1 inside each quad: quad_perm [1, 0, 3, 2])
+          const uint32_t p = (uint32_t)__builtin_amdgcn_mov_dpp((int)we, 0xB1, 0xF, 0xF, true);
+          vt[vdst[j][e]] = __builtin_amdgcn_perm(p, we, vsel);
         }
       }
     }

@@ -98,6 +98,8 @@ int check_layer_args(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w
   if (!w->ln1_g || !w->ln1_b || !w->w_qkv || !w->w_o || !w->ln2_g || !w->ln2_b || !w->w_fc1 || !w->w_fc2)
     return ENERGON_ERR_NULL;
   if (B <= 0 || B > 65535 || max_len <= 0 || T < 0) return ENERGON_ERR_SHAPE;
+  // the attention kernels address one sequence's rows with 32-bit byte offsets
+  if ((int64_t)max_len * 3 * cfg->n_heads * cfg->head_dim * esize(cfg->dtype) >= ((int64_t)1 << 32)) return ENERGON_ERR_UNSUPPORTED;
   int64_t total = 0;
   st = check_lengths(lengths, B, max_len, &total);
   if (st != ENERGON_OK) return st;
@@ -358,6 +360,7 @@ int energon_attention(const void* qkv, void* out, const int32_t* cu, int64_t T, 
   if (head_dim != 64 && head_dim != 128) return ENERGON_ERR_UNSUPPORTED;
   if (B <= 0 || max_len <= 0 || n_heads <= 0 || T < 0 || T >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
   if (B > 65535 || n_heads > 65535) return ENERGON_ERR_UNSUPPORTED;
+  if ((int64_t)max_len * 3 * n_heads * head_dim * esize(dtype) >= ((int64_t)1 << 32)) return ENERGON_ERR_UNSUPPORTED;
   if (!aligned16(qkv) || !aligned16(out) || (reinterpret_cast<uintptr_t>(cu) & 3u)) return ENERGON_ERR_ALIGN;
   if (T == 0) return ENERGON_OK;
   return attention_impl(qkv, out, cu, B, max_len, n_heads, head_dim, dtype, static_cast<hipStream_t>(stream));
