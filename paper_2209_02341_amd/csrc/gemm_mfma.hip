@@ -4,25 +4,26 @@
 //
 // Design for gfx950:
 //  * both operands are contiguous along K, so x rows feed the MFMA A operand and W rows the
-//    B operand with the same 16-byte chunks; v_mfma_f32_32x32x16_bf16, fp32 accumulators;
+//    B operand with the same 16-byte chunks; fp32 accumulators;
 //  * a BM x BN output tile per workgroup, K walked in slabs of 64 (128 bytes per row), two
-//    slab buffers in LDS;
-//  * an LDS row is 8 chunks of 16 bytes; chunk c of row r is stored in slot c ^ swz(r), so the
-//    32 rows a wavefront reads for one MFMA operand fall in distinct banks (measured: zero bank
-//    conflicts).  Slabs are moved in 1 KiB groups = 8 rows x 8 slots in lane order, the lane that
-//    lands in slot s of row r fetching chunk s ^ swz(r): full 128-byte lines on the global side;
+//    slab buffers in LDS, filled straight from global memory (global_load_lds_dwordx4);
+//  * an LDS row is 8 chunks of 16 bytes; chunk c of row r is stored in slot c ^ swizzle(r), chosen
+//    per MFMA form so that a wavefront's operand read meets no bank conflict (measured).  Slabs
+//    are moved in 1 KiB groups = 8 rows x 8 slots in lane order, the lane that lands in slot s of
+//    row r fetching chunk s ^ swizzle(r): full 128-byte lines on the global side;
 //  * workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2, so the id is
 //    remapped to give every XCD a contiguous run of tiles, ordered in bands of 8 row tiles:
 //    the 32 tiles resident on an XCD form an 8 x 4 block that shares x and W slabs in that L2;
-//  * epilogue in fp32: + bias, GeLU(erf) or + residual, one rounding to bf16.
+//  * epilogue in fp32: + bias, GeLU(erf) or + residual, one rounding to the storage type.
 // Two kernels:
-//  * gemm_bf16_sched_kernel, 256x256 tile, 4 wavefronts x 128x128 with the 256 accumulators in
-//    AGPRs, slab loop hand-scheduled; slab chunks are fetched into registers four slabs ahead and
-//    written to LDS two slabs ahead (a two-slab load window); edge tiles are shifted inwards, so
-//    nothing is clamped or predicated; the epilogue goes through LDS and leaves as 16-byte stores;
-//  * gemm_bf16_tile_kernel, compiler-scheduled, direct-to-LDS loads (global_load_lds_dwordx4),
-//    clamped loads and predicated stores: used with 128x128 tiles for everything the first
-//    kernel does not take (small or ragged-below-one-tile problems, odd slab counts).
+//  * gemm_mfma_sched_kernel, 256x256 tile, 4 wavefronts x 128x128 = 8 x 8 tiles of
+//    v_mfma_f32_16x16x32 with the 256 accumulators in AGPRs; the slab loop is hand-scheduled
+//    (MFMA, LDS reads and the next slab's loads interleaved in asm); edge tiles are shifted
+//    inwards, so nothing is clamped or predicated; the epilogue goes through LDS and leaves as
+//    16-byte non-temporal stores;
+//  * gemm_mfma_tile_kernel, compiler-scheduled, v_mfma_f32_32x32x16, clamped loads and predicated
+//    stores: used with 128x128 tiles for everything the first kernel does not take (small or
+//    ragged-below-one-tile problems, odd slab counts).
 #include "common.h"
 
 namespace energon {
@@ -43,6 +44,12 @@ typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// The same for the 16-row operand tiles of the 16x16x32 form, where lane l reads row l % 16, chunk
+// 4 ks + l / 16: row bits 1, 2, 3 go to slot bits 0, 2, 1 (measured: zero bank conflicts; with the
+// function above every such read takes two passes).
+__device__ __forceinline__ int swz16(int row) {
+  return ((row >> 1) & 1) | (((row >> 2) & 1) << 2) | (((row >> 3) & 1) << 1);
+}
 
 // XCD-aware tile order; false if this workgroup is one of the (< 8) padding ids.
 template <int BM, int BN>
@@ -331,7 +338,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   uint32_t aaddr[2], baddr[2];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
-    const uint32_t chunk = (uint32_t)((ks * 4 + lq) ^ swz(lrow)) * 16u;
+    const uint32_t chunk = (uint32_t)((ks * 4 + lq) ^ swz16(lrow)) * 16u;
     aaddr[ks] = (uint32_t)(wm0 + lrow) * 128u + chunk;
     baddr[ks] = (uint32_t)(BM + wn0 + lrow) * 128u + chunk;
   }
@@ -360,7 +367,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   // half that reads them -- AL / AH: x rows 0..63 / 64..127 of each wavefront row, BL / BH likewise
   // for W -- and every wavefront moves 4 groups of each class, of its own parity (swz(row) depends
   // on row % 16 = 8 * (group parity) + l / 8, so one per-lane offset serves all its groups).
-  const uint32_t voff = ((uint32_t)(lane >> 3) * (uint32_t)K + (uint32_t)(((lane & 7) ^ swz((wave & 1) * 8 + (lane >> 3))) * 8)) * 2u;
+  const uint32_t voff = ((uint32_t)(lane >> 3) * (uint32_t)K + (uint32_t)(((lane & 7) ^ swz16((wave & 1) * 8 + (lane >> 3))) * 8)) * 2u;
   const char* gsrc[4][4];  // [class AL, BH, BL, AH][j]: global address of the group's first row, slab 0
   uint32_t ldst[4][4];     // its LDS byte offset in buffer 0
 #pragma unroll
