@@ -30,7 +30,9 @@ Pins (tests/test_oracle_*.py): brute-force unbatched runs, padding invariance,
 hand-computed one-token/one-head values, position-0 closed form, uniform-attention
 closed form, identity block with zero output weights, per-stage agreement with
 textbook library routines, and (for the paper's padded attention path) round trips,
-closed-form indices and agreement with the variable-length attention on valid tokens.
+closed-form indices and agreement with the variable-length attention on valid tokens; for
+the LayerNorm-folded linear, the identity against layer_norm + linear, a hand-computed 2x2
+case and the rounding rule for its column sums.
 No function here is "parity unpinned".
 """
 import numpy as np
@@ -82,6 +84,38 @@ def unpack(x_packed, lengths, S):
     out[idx] = x_packed
     return out.reshape(B, S, H)
 
+
+
+# ----------------------------------------------------- LayerNorm folded into the next linear
+# The fusion the paper credits to the comparison system (Sec. 5.5: LayerNorm, the QKV
+# contractions and the bias in one kernel), in the algebraic form the HIP path uses.  With
+# mu, r = row mean and 1/sqrt(var + eps) of x:
+#   linear(layer_norm(x), W, b) = r * (x @ Wf^T - mu * c) + bf,
+#   Wf = W * gamma (per input feature),  c = Wf summed over the input features,  bf = b + W @ beta.
+# The definition of the result stays linear(layer_norm(x, ...), W, b); these two functions
+# state the pieces the fused kernels exchange, so that each piece can be compared on its own.
+def row_stats(x, eps):
+    """(mean, 1/sqrt(biased variance + eps)) of every row."""
+    mu = x.mean(axis=-1)
+    var = ((x - mu[:, None]) ** 2).mean(axis=-1)
+    return mu, 1.0 / np.sqrt(var + eps)
+
+
+def fold_layer_norm(w, b, gamma, beta, round_weights=None):
+    """(Wf, c, bf) as above.  `round_weights`, if given, is applied to Wf before c is summed:
+    the identity must hold for the weights the contraction really uses, so a 16-bit Wf has its
+    column sums taken after the rounding."""
+    wf = w * gamma[None, :]
+    if round_weights is not None:
+        wf = round_weights(wf)
+    c = wf.sum(axis=1)
+    bf = w @ beta + (0.0 if b is None else b)
+    return wf, c, bf
+
+
+def linear_ln_folded(x, wf, c, bf, mu, r):
+    """r * (x @ Wf^T - mu * c) + bf, the right-hand side of the identity."""
+    return r[:, None] * (x @ wf.T - mu[:, None] * c[None, :]) + bf[None, :]
 
 # --------------------------------------------------------------------------- stages
 def layer_norm(x, gamma, beta, eps):
