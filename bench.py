@@ -11,6 +11,7 @@ the timed region.  Prints ONE JSON line:
   padded     the same library run with every position treated as valid (no elimination)
   paper_attention_path  the layer with the attention stage done the paper's way (padded core
              between a rebuild-padding and a remove-padding transpose kernel)
+  ln_folded  the same step with both LayerNorms folded into the contractions that follow them
   cpu_baseline  the CPU oracle timed on a bounded sample of whole sequences, one layer
 """
 import argparse
@@ -41,6 +42,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
     ap.add_argument("--no-paper-path", action="store_true")
+    ap.add_argument("--no-ln-folded", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -74,17 +76,21 @@ def main():
     log("[bench] inputs resident on the GPU")
     cfg = hz.layer_config(H, w.n_heads, w.head_dim, F, w.dtype, w.ln_eps)
 
-    def time_steps(run, lengths, steps, warmup):
+    def time_steps(run, lengths, steps, warmup, folded=None):
         # wall clock over exactly `steps` steps between two synchronisations; per-step durations from
         # HIP events on the launch stream (for the median and the minimum)
+        if folded is not None:
+            fwd = lambda: run.forward_folded(x_dev, lengths, folded)
+        else:
+            fwd = lambda: run.forward(x_dev, lengths, dev_layers)
         for _ in range(warmup):
-            run.forward(x_dev, lengths, dev_layers)
+            fwd()
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         marks[0].record()
         for i in range(steps):
-            run.forward(x_dev, lengths, dev_layers)
+            fwd()
             marks[i + 1].record()
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) / steps * 1e3
@@ -172,6 +178,20 @@ def main():
             f"(variable-length: {stage_ms['attn']:.3f}); layer {sum(acc.values()):.3f} vs {sum(stage_ms.values()):.3f} ms")
         del padws
 
+    # ---- LayerNorm folded into the QKV and FC1 contractions (Sec. 5.5's fusion, algebraic form):
+    # same step, folded weights, no normalised activation written, row statistics from the
+    # residual epilogues ----
+    ln_folded = None
+    if w.dtype != wl.F32 and not args.no_ln_folded:
+        folded_layers = [hz.FoldedDeviceLayer(d) for d in dev_layers]
+        ms_f, ms_f_median, ms_f_min = time_steps(run, lens, args.steps, min(args.warmup, 2), folded=folded_layers)
+        ln_folded = {"ms_per_step": ms_f, "ms_per_step_median": ms_f_median, "ms_per_step_min": ms_f_min,
+                     "value": T / (ms_f / L * 1e-3), "speedup_over_unfused": ms_step / ms_f,
+                     "unfused_layernorm_ms_per_layer": stage_ms["ln1"] + stage_ms["ln2"]}
+        log(f"[bench] LayerNorm folded: {ms_f:.3f} ms/step (median {ms_f_median:.3f}) vs {ms_step:.3f} unfused "
+            f"({ms_step / ms_f:.3f}x)")
+        del folded_layers
+
     # ---- padded (no-elimination) path: same library, every position valid ----
     padded = None
     if not args.no_padded:
@@ -228,7 +248,7 @@ def main():
                      "flops_per_launch": gemm_flops_layer / 4},
         "stage_ms_per_layer": stage_ms, "stage_tflops": stage_tflops,
         "pack_ms": pack_ms, "unpack_ms": unpack_ms, "hbm": hbm,
-        "padded": padded, "paper_attention_path": paper_path, "cpu_baseline": cpu,
+        "padded": padded, "paper_attention_path": paper_path, "ln_folded": ln_folded, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 

@@ -228,6 +228,68 @@ int energon_layer_forward_drce(const EnergonLayerConfig* cfg, const EnergonLayer
                                void* pad_workspace_dev, size_t pad_workspace_bytes, void* stream,
                                float* stage_ms_host);
 
+/* ---- LayerNorm folded into the linear that follows it (bf16 / fp16) -------------------------
+ * Sec. 5.5 of the paper names the fusion of LayerNorm with the QKV contractions and the bias as
+ * what the comparison system gains over unfused operators.  Here the fusion is algebraic: with
+ * mu, r = mean and 1/sqrt(var + eps) of a row of x,
+ *     LayerNorm(x) W^T + b  =  r (x Wf^T - mu c) + bf,
+ *     Wf = W gamma (per input feature),  c[n] = sum_k Wf[n,k],  bf = b + W beta,
+ * so the contraction reads the un-normalised rows and the normalised matrix is never written.
+ * All pointers below are device pointers; fp32 arrays need 16-byte alignment like the rest. */
+
+/* Once per weight matrix: w [N,K], b [N] or NULL, gamma, beta [K] (element type = dtype) ->
+ * w_folded [N,K] (same type, may not alias w), colsum [N] and bias_folded [N] in fp32.  colsum is
+ * taken from the rounded w_folded.  K % 8 == 0.  ENERGON_ERR_UNSUPPORTED for fp32. */
+int energon_fold_layernorm(const void* w, const void* b, const void* gamma, const void* beta, int32_t N, int32_t K,
+                           int32_t dtype, void* w_folded, float* colsum, float* bias_folded, void* stream);
+
+/* stats[m] = (mean, 1/sqrt(biased variance + eps)) of row m of x [M,K], fp32 pairs.
+ * K % 8 == 0, K <= 32768.  M = 0 is a no-op. */
+int energon_row_stats(const void* x, int64_t M, int32_t K, int32_t dtype, float eps, float* stats, void* stream);
+
+/* y [M,N] = act( stats[m].r * (x Wf^T - stats[m].mean * colsum) + bias_folded ), act = GeLU (exact
+ * erf form) if gelu != 0, else identity.  Shape rules of energon_linear. */
+int energon_linear_ln_folded(const void* x, const void* w_folded, const float* colsum, const float* bias_folded,
+                             const float* stats, void* y, int64_t M, int32_t N, int32_t K, int32_t gelu,
+                             int32_t dtype, void* stream);
+
+/* Bytes of scratch energon_linear_residual_stats may use: one (sum, squared deviations) pair per
+ * row and 128 output columns. */
+size_t energon_stats_scratch_bytes(int64_t M, int32_t N);
+
+/* y = residual + x W^T + b as energon_linear does, and stats_out[m] = row statistics (as
+ * energon_row_stats) of the ROUNDED y: taken in the contraction's epilogue plus a merge kernel
+ * where the launch shape allows (whole 256-column tiles, enough tiles), otherwise by a pass over
+ * y.  scratch: energon_stats_scratch_bytes(M, N) bytes, 256-byte aligned, contents undefined
+ * afterwards.  N % 8 == 0, N <= 32768. */
+int energon_linear_residual_stats(const void* x, const void* w, const void* bias, const void* residual, void* y,
+                                  int64_t M, int32_t N, int32_t K, int32_t dtype, float eps, float* stats_out,
+                                  void* scratch, size_t scratch_bytes, void* stream);
+
+/* One layer's parameters with both LayerNorms folded (energon_fold_layernorm of w_qkv with
+ * ln1 and of w_fc1 with ln2); w_o, b_o, w_fc2, b_fc2 as in EnergonLayerWeights. */
+typedef struct {
+  const void* wf_qkv;            /* [3A, H] */
+  const float *c_qkv, *bf_qkv;   /* [3A]    */
+  const void *w_o, *b_o;         /* [H, A], [H] or NULL */
+  const void* wf_fc1;            /* [F, H]  */
+  const float *c_fc1, *bf_fc1;   /* [F]     */
+  const void *w_fc2, *b_fc2;     /* [H, F], [H] or NULL */
+} EnergonFoldedLayerWeights;
+
+/* energon_layer_forward on folded weights: row statistics -> QKV (folded) -> attention ->
+ * out-proj + residual (statistics from its epilogue) -> FC1 (folded) + GeLU -> FC2 + residual.
+ * No normalised activation is written; the workspace (same size and alignment as for
+ * energon_layer_forward) holds the statistics in the two regions that path uses for them.
+ * stats_in: row statistics of x_packed [T][2] if the caller has them (the previous layer's
+ * stats_out), else NULL and they are computed here.  stats_out: if not NULL, receives the row
+ * statistics of y_packed for the next layer.  cfg->hidden <= 32768.  bf16 / fp16 only. */
+int energon_layer_forward_ln_folded(const EnergonLayerConfig* cfg, const EnergonFoldedLayerWeights* weights,
+                                    const void* x_packed_dev, void* y_packed_dev, int64_t T,
+                                    const int32_t* cu_seqlens_dev, const int32_t* lengths_host, int32_t B,
+                                    int32_t max_len, void* workspace_dev, size_t workspace_bytes,
+                                    const float* stats_in, float* stats_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

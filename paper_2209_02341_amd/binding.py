@@ -39,6 +39,13 @@ class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
 
 
+_FOLDED_FIELDS = ("wf_qkv", "c_qkv", "bf_qkv", "w_o", "b_o", "wf_fc1", "c_fc1", "bf_fc1", "w_fc2", "b_fc2")
+
+
+class FoldedLayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _FOLDED_FIELDS]
+
+
 _lib = None
 
 
@@ -71,6 +78,17 @@ def lib() -> C.CDLL:
         l.energon_drce_workspace_bytes.restype = sz
         l.energon_drce_workspace_bytes.argtypes = [pcfg, i32, i32]
         l.energon_layer_forward_drce.argtypes = layer_args[:-1] + [vp, sz, vp, C.POINTER(C.c_float)]
+        l.energon_fold_layernorm.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
+        l.energon_row_stats.argtypes = [vp, i64, i32, i32, C.c_float, vp, vp]
+        l.energon_linear_ln_folded.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
+        l.energon_stats_scratch_bytes.restype = sz
+        l.energon_stats_scratch_bytes.argtypes = [i64, i32]
+        l.energon_linear_residual_stats.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, C.c_float, vp, vp, sz, vp]
+        l.energon_layer_forward_ln_folded.argtypes = [pcfg, C.POINTER(FoldedLayerWeights), vp, vp, i64, vp, vp, i32,
+                                                      i32, vp, sz, vp, vp, vp]
+        for name in ("energon_fold_layernorm", "energon_row_stats", "energon_linear_ln_folded",
+                     "energon_linear_residual_stats", "energon_layer_forward_ln_folded"):
+            getattr(l, name).restype = C.c_int
         for name in ("energon_workspace_layout", "energon_pack", "energon_unpack", "energon_layer_forward",
                      "energon_layer_forward_profiled", "energon_layernorm", "energon_linear",
                      "energon_attention", "energon_rebuild_qkv", "energon_attention_padded",
@@ -124,6 +142,15 @@ def make_weights(tensors: dict) -> LayerWeights:
     keeps the tensors alive."""
     w = LayerWeights()
     for n in _WEIGHT_FIELDS:
+        setattr(w, n, _ptr(tensors.get(n)))
+    return w
+
+
+def make_folded_weights(tensors: dict) -> FoldedLayerWeights:
+    """FoldedLayerWeights from a dict of device tensors (missing / None bias = NULL).  The caller
+    keeps the tensors alive."""
+    w = FoldedLayerWeights()
+    for n in _FOLDED_FIELDS:
         setattr(w, n, _ptr(tensors.get(n)))
     return w
 
@@ -240,3 +267,50 @@ def energon_layer_forward_drce(cfg: LayerConfig, weights: LayerWeights, x_packed
                                             int(pad_workspace.numel() * pad_workspace.element_size()),
                                             _stream(stream), ms), "energon_layer_forward_drce")
     return dict(zip(STAGE_NAMES, (float(v) for v in ms))) if timed else None
+
+
+# ---- LayerNorm folded into the following linear
+def energon_fold_layernorm(w, b, gamma, beta, w_folded, colsum, bias_folded, stream=None) -> None:
+    N, K = w.shape
+    _check(lib().energon_fold_layernorm(_ptr(w), _ptr(b), _ptr(gamma), _ptr(beta), N, K, _dtype_code(w),
+                                        _ptr(w_folded), _ptr(colsum), _ptr(bias_folded), _stream(stream)),
+           "energon_fold_layernorm")
+
+
+def energon_row_stats(x, eps: float, stats, stream=None) -> None:
+    M, K = x.shape
+    _check(lib().energon_row_stats(_ptr(x), M, K, _dtype_code(x), float(eps), _ptr(stats), _stream(stream)),
+           "energon_row_stats")
+
+
+def energon_linear_ln_folded(x, w_folded, colsum, bias_folded, stats, y, gelu: bool, stream=None) -> None:
+    M, K = x.shape
+    N = w_folded.shape[0]
+    _check(lib().energon_linear_ln_folded(_ptr(x), _ptr(w_folded), _ptr(colsum), _ptr(bias_folded), _ptr(stats),
+                                          _ptr(y), M, N, K, int(bool(gelu)), _dtype_code(x), _stream(stream)),
+           "energon_linear_ln_folded")
+
+
+def energon_stats_scratch_bytes(M: int, N: int) -> int:
+    return int(lib().energon_stats_scratch_bytes(int(M), int(N)))
+
+
+def energon_linear_residual_stats(x, w, bias, residual, y, eps: float, stats_out, scratch, stream=None) -> None:
+    M, K = x.shape
+    N = w.shape[0]
+    _check(lib().energon_linear_residual_stats(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K,
+                                               _dtype_code(x), float(eps), _ptr(stats_out), _ptr(scratch),
+                                               int(scratch.numel() * scratch.element_size()), _stream(stream)),
+           "energon_linear_residual_stats")
+
+
+def energon_layer_forward_ln_folded(cfg: LayerConfig, weights: FoldedLayerWeights, x_packed, y_packed, T: int,
+                                    cu_seqlens, lengths, max_len: int, workspace, stats_in=None, stats_out=None,
+                                    stream=None) -> None:
+    lens = _lengths(lengths)
+    _check(lib().energon_layer_forward_ln_folded(C.byref(cfg), C.byref(weights), _ptr(x_packed), _ptr(y_packed),
+                                                 int(T), _ptr(cu_seqlens), _ptr(lens), len(lens), int(max_len),
+                                                 _ptr(workspace),
+                                                 int(workspace.numel() * workspace.element_size()),
+                                                 _ptr(stats_in), _ptr(stats_out), _stream(stream)),
+           "energon_layer_forward_ln_folded")

@@ -68,24 +68,47 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
-// GeLU in its erf form, z * Phi(z) = 0.5 z (1 + erf(z / sqrt 2)), in fp32.  erf is evaluated
-// branch-free with the rational approximation 7.1.26 of Abramowitz & Stegun,
-//   erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),  t = 1 / (1 + p x),  x >= 0,  |error| <= 1.5e-7,
-// i.e. an absolute error of at most 7.5e-8 |z| on GeLU: two transcendental instructions and a
-// dozen FMAs instead of the library erff's two divergent code paths.
+// GeLU in its erf form, z * Phi(z) = 0.5 z (1 + erf(z / sqrt 2)), in fp32, written without the
+// cancellation of 1 + erf for negative z:
+//   GeLU(z) = max(z, 0) - 0.5 |z| erfc(|z| / sqrt 2),
+// with erfc(|z| / sqrt 2) = 2^P(|z|), P a degree-7 polynomial without constant term.  Its
+// coefficients are a weighted least-squares fit (reweighted towards the minimax solution) of
+// log2 erfc on 0 <= |z| <= 7.35, weighted by the error the term leaves on GeLU, with the leading
+// coefficient held negative so that P -> -inf and 2^P -> 0 beyond the fitted range.  Absolute
+// error on GeLU <= 1.3e-7 before the final fp32 rounding (a host-side test re-evaluates these
+// constants against a library erf); one transcendental instruction and ten multiply-adds per
+// element, branch-free, |z| taken as an operand modifier.
+constexpr float kGeluErfcPoly[7] = {-1.1511532068252563f,    -0.4588780403137207f,   -0.05332031473517418f,
+                                    0.008061456494033337f,   -0.0007832530536688864f, 4.081824226886965e-05f,
+                                    -1.0515688018131186e-06f};
 __device__ inline float gelu_erf(float z) {
-  const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  const float e = __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
-  const float erf_abs = fmaf(-p * t, e, 1.0f);           // erf(|z| / sqrt 2)
-  return 0.5f * z * (1.0f + copysignf(erf_abs, z));
+  const float a = fabsf(z);
+  float p = fmaf(kGeluErfcPoly[6], a, kGeluErfcPoly[5]);
+  p = fmaf(p, a, kGeluErfcPoly[4]);
+  p = fmaf(p, a, kGeluErfcPoly[3]);
+  p = fmaf(p, a, kGeluErfcPoly[2]);
+  p = fmaf(p, a, kGeluErfcPoly[1]);
+  p = fmaf(p, a, kGeluErfcPoly[0]);
+  const float e = __builtin_amdgcn_exp2f(p * a);   // erfc(|z| / sqrt 2)
+  return fmaf(-0.5f * a, e, fmaxf(z, 0.f));
 }
 
-enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2 };
+enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_LNFOLD = 3, EPI_LNFOLD_GELU = 4 };
+
+// LayerNorm folded into a 16-bit linear (the fusion of Sec. 5.5's comparison system, in algebraic
+// form): with mean mu and r = 1/sqrt(var + eps) of an x row,
+//   LayerNorm(x) W^T + b = r (x Wf^T - mu c) + bf,   Wf = W gamma,  c = row sums of Wf,  bf = b + W beta.
+// EPI_LNFOLD / EPI_LNFOLD_GELU read stats, colsum and bias (fp32); the E-typed bias is unused.
+// With EPI_BIAS_RESIDUAL, a non-null `partial` receives, per output row and 128-column segment,
+// (sum, sum of squared deviations from the segment mean) of the ROUNDED outputs: the next
+// LayerNorm's statistics without another pass over the row.  Null members = feature unused.
+constexpr int kStatSeg = 128;  // columns per partial
+struct LnFold {
+  const float* stats = nullptr;   // [M][2] mu, r
+  const float* colsum = nullptr;  // [N]
+  const float* bias = nullptr;    // [N]
+  float* partial = nullptr;       // [M][N / kStatSeg][2]
+};
 
 // ---- launchers (each returns the hipError_t of its launch) --------------------------------
 // pack.hip
@@ -101,10 +124,17 @@ hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, 
 // gemm_f32.hip / gemm_mfma.hip (16-bit element types on the matrix cores)
 hipError_t launch_gemm_f32(const float* x, const float* w, const float* bias, const float* res, float* y,
                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
+// true if the launch for this shape can fill LnFold::partial (else the caller takes the statistics itself)
+bool gemm_emits_row_partials(int64_t M, int32_t N, int32_t K, bool res_aliases_y);
 hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
-                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
+                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
 hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y,
-                           int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
+                           int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
+// ln_fold.hip (dtype 1 or 2 only)
+hipError_t launch_fold_weights(const void* w, const void* b, const void* gamma, const void* beta, int32_t N, int32_t K,
+                               int dtype, void* wf, float* colsum, float* bias_f, hipStream_t s);
+hipError_t launch_row_stats(const void* x, int64_t M, int32_t K, float eps, int dtype, float* stats, hipStream_t s);
+hipError_t launch_merge_partials(const float* partial, int64_t M, int32_t P, float eps, float* stats, hipStream_t s);
 // attention_f32.hip / attention_mfma.hip
 hipError_t launch_attention_f32(const float* qkv, float* out, const int32_t* cu, int32_t B, int32_t max_len,
                                 int32_t nh, int32_t d, hipStream_t s);

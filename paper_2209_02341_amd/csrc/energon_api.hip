@@ -54,13 +54,15 @@ WsLayout ws_layout(const EnergonLayerConfig* c, int64_t T) {
 }
 
 int linear_impl(const void* x, const void* w, const void* bias, const void* res, void* y, int64_t M, int32_t N,
-                int32_t K, int32_t epi, int32_t dt, hipStream_t s) {
+                int32_t K, int32_t epi, int32_t dt, hipStream_t s, const LnFold* fold = nullptr) {
   if (dt == ENERGON_BF16)
     HIP_TRY(launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, (const bf16_t*)res, (bf16_t*)y,
-                             M, N, K, epi, s));
+                             M, N, K, epi, s, fold));
   else if (dt == ENERGON_F16)
     HIP_TRY(launch_gemm_f16((const f16_t*)x, (const f16_t*)w, (const f16_t*)bias, (const f16_t*)res, (f16_t*)y, M, N,
-                            K, epi, s));
+                            K, epi, s, fold));
+  else if (fold != nullptr)
+    return ENERGON_ERR_UNSUPPORTED;
   else
     HIP_TRY(launch_gemm_f32((const float*)x, (const float*)w, (const float*)bias, (const float*)res, (float*)y, M, N,
                             K, epi, s));
@@ -159,6 +161,63 @@ int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, cons
   STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, T, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
   MARK(7);
 #undef MARK
+#undef STEP
+  return ENERGON_OK;
+}
+
+// y = res + x W^T + b with the row statistics of the rounded y: from the epilogue's partials where
+// the launch can produce them, else by a pass over y.  `partials` holds M * (N / 128) pairs.
+int linear_residual_stats(const void* x, const void* w, const void* bias, const void* res, void* y, int64_t M,
+                          int32_t N, int32_t K, int32_t dt, float eps, float* stats_out, float* partials,
+                          hipStream_t s) {
+  if (gemm_emits_row_partials(M, N, K, res == y)) {
+    LnFold lf;
+    lf.partial = partials;
+    const int st = linear_impl(x, w, bias, res, y, M, N, K, ENERGON_EPI_BIAS_RESIDUAL, dt, s, &lf);
+    if (st != ENERGON_OK) return st;
+    HIP_TRY(launch_merge_partials(partials, M, N / kStatSeg, eps, stats_out, s));
+    return ENERGON_OK;
+  }
+  const int st = linear_impl(x, w, bias, res, y, M, N, K, ENERGON_EPI_BIAS_RESIDUAL, dt, s);
+  if (st != ENERGON_OK) return st;
+  HIP_TRY(launch_row_stats(y, M, N, eps, dt, stats_out, s));
+  return ENERGON_OK;
+}
+
+// The block on folded weights (see energon_layer_forward_ln_folded).  The regions of the
+// workspace that the unfused path fills with normalised activations hold the partials (U) and
+// the two statistics arrays (W) instead.
+int layer_folded_impl(const EnergonLayerConfig* cfg, const EnergonFoldedLayerWeights* w, const void* x, void* y,
+                      int64_t T, const int32_t* cu, int32_t B, int32_t max_len, void* ws, const float* stats_in,
+                      float* stats_out, hipStream_t s) {
+  const WsLayout l = ws_layout(cfg, T);
+  char* base = static_cast<char*>(ws);
+  float* partials = reinterpret_cast<float*>(base + l.off[ENERGON_WS_U]);
+  void* qkv = base + l.off[ENERGON_WS_QKV];
+  void* att = base + l.off[ENERGON_WS_ATTN];
+  void* y1 = base + l.off[ENERGON_WS_Y1];
+  float* stats1 = reinterpret_cast<float*>(base + l.off[ENERGON_WS_W]);
+  float* stats2 = stats1 + 2 * (size_t)T;
+  void* m = base + l.off[ENERGON_WS_M];
+  const int32_t H = cfg->hidden, A = cfg->n_heads * cfg->head_dim, F = cfg->ffn, dt = cfg->dtype;
+  int st;
+#define STEP(call) do { st = (call); if (st != ENERGON_OK) return st; } while (0)
+  if (stats_in == nullptr) {
+    HIP_TRY(launch_row_stats(x, T, H, cfg->ln_eps, dt, stats1, s));
+    stats_in = stats1;
+  }
+  LnFold f1;
+  f1.stats = stats_in; f1.colsum = w->c_qkv; f1.bias = w->bf_qkv;
+  STEP(linear_impl(x, w->wf_qkv, nullptr, nullptr, qkv, T, 3 * A, H, EPI_LNFOLD, dt, s, &f1));
+  if (T > 0) STEP(attention_impl(qkv, att, cu, B, max_len, cfg->n_heads, cfg->head_dim, dt, s));
+  STEP(linear_residual_stats(att, w->w_o, w->b_o, x, y1, T, H, A, dt, cfg->ln_eps, stats2, partials, s));
+  LnFold f2;
+  f2.stats = stats2; f2.colsum = w->c_fc1; f2.bias = w->bf_fc1;
+  STEP(linear_impl(y1, w->wf_fc1, nullptr, nullptr, m, T, F, H, EPI_LNFOLD_GELU, dt, s, &f2));
+  if (stats_out != nullptr)
+    STEP(linear_residual_stats(m, w->w_fc2, w->b_fc2, y1, y, T, H, F, dt, cfg->ln_eps, stats_out, partials, s));
+  else
+    STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, T, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
 #undef STEP
   return ENERGON_OK;
 }
@@ -364,6 +423,99 @@ int energon_attention(const void* qkv, void* out, const int32_t* cu, int64_t T, 
   if (!aligned16(qkv) || !aligned16(out) || (reinterpret_cast<uintptr_t>(cu) & 3u)) return ENERGON_ERR_ALIGN;
   if (T == 0) return ENERGON_OK;
   return attention_impl(qkv, out, cu, B, max_len, n_heads, head_dim, dtype, static_cast<hipStream_t>(stream));
+}
+
+int energon_fold_layernorm(const void* w, const void* b, const void* gamma, const void* beta, int32_t N, int32_t K,
+                           int32_t dtype, void* w_folded, float* colsum, float* bias_folded, void* stream) {
+  if (!w || !gamma || !beta || !w_folded || !colsum || !bias_folded) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (N <= 0 || K <= 0 || K % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (w == w_folded) return ENERGON_ERR_UNSUPPORTED;
+  if (!aligned16(w) || !aligned16(gamma) || !aligned16(beta) || !aligned16(w_folded) || !aligned16(colsum) ||
+      !aligned16(bias_folded) || (reinterpret_cast<uintptr_t>(b) & 1u))
+    return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_fold_weights(w, b, gamma, beta, N, K, dtype, w_folded, colsum, bias_folded,
+                              static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_row_stats(const void* x, int64_t M, int32_t K, int32_t dtype, float eps, float* stats, void* stream) {
+  if (!x || !stats) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (M < 0 || M >= ((int64_t)1 << 31) || K <= 0 || K % 8 != 0 || !(eps >= 0.f)) return ENERGON_ERR_SHAPE;
+  if (K > 32768) return ENERGON_ERR_UNSUPPORTED;
+  if (!aligned16(x) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_row_stats(x, M, K, eps, dtype, stats, static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_linear_ln_folded(const void* x, const void* w_folded, const float* colsum, const float* bias_folded,
+                             const float* stats, void* y, int64_t M, int32_t N, int32_t K, int32_t gelu,
+                             int32_t dtype, void* stream) {
+  if (!x || !w_folded || !colsum || !bias_folded || !stats || !y) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0) return ENERGON_ERR_SHAPE;
+  if (K % 64 != 0 || N % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (!aligned16(x) || !aligned16(w_folded) || !aligned16(colsum) || !aligned16(bias_folded) || !aligned16(y) ||
+      (reinterpret_cast<uintptr_t>(stats) & 7u))
+    return ENERGON_ERR_ALIGN;
+  LnFold lf;
+  lf.stats = stats; lf.colsum = colsum; lf.bias = bias_folded;
+  return linear_impl(x, w_folded, nullptr, nullptr, y, M, N, K, gelu ? EPI_LNFOLD_GELU : EPI_LNFOLD, dtype,
+                     static_cast<hipStream_t>(stream), &lf);
+}
+
+size_t energon_stats_scratch_bytes(int64_t M, int32_t N) {
+  if (M < 0 || N <= 0) return 0;
+  const size_t b = round256((size_t)M * (size_t)((N + kStatSeg - 1) / kStatSeg) * 2 * sizeof(float));
+  return b ? b : 256;
+}
+
+int energon_linear_residual_stats(const void* x, const void* w, const void* bias, const void* residual, void* y,
+                                  int64_t M, int32_t N, int32_t K, int32_t dtype, float eps, float* stats_out,
+                                  void* scratch, size_t scratch_bytes, void* stream) {
+  if (!x || !w || !residual || !y || !stats_out || !scratch) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0 || !(eps >= 0.f)) return ENERGON_ERR_SHAPE;
+  if (K % 64 != 0 || N % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (N > 32768) return ENERGON_ERR_UNSUPPORTED;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(y) ||
+      (reinterpret_cast<uintptr_t>(stats_out) & 7u) || (reinterpret_cast<uintptr_t>(scratch) & 255u))
+    return ENERGON_ERR_ALIGN;
+  if (scratch_bytes < energon_stats_scratch_bytes(M, N)) return ENERGON_ERR_CAPACITY;
+  return linear_residual_stats(x, w, bias, residual, y, M, N, K, dtype, eps, stats_out, static_cast<float*>(scratch),
+                               static_cast<hipStream_t>(stream));
+}
+
+int energon_layer_forward_ln_folded(const EnergonLayerConfig* cfg, const EnergonFoldedLayerWeights* w, const void* x,
+                                    void* y, int64_t T, const int32_t* cu, const int32_t* lengths, int32_t B,
+                                    int32_t max_len, void* ws, size_t ws_bytes, const float* stats_in,
+                                    float* stats_out, void* stream) {
+  int st = check_cfg(cfg);
+  if (st != ENERGON_OK) return st;
+  if (!is16(cfg->dtype) || cfg->hidden > 32768) return ENERGON_ERR_UNSUPPORTED;
+  if (!w || !x || !y || !cu || !lengths || !ws) return ENERGON_ERR_NULL;
+  if (!w->wf_qkv || !w->c_qkv || !w->bf_qkv || !w->w_o || !w->wf_fc1 || !w->c_fc1 || !w->bf_fc1 || !w->w_fc2)
+    return ENERGON_ERR_NULL;
+  if (B <= 0 || B > 65535 || max_len <= 0 || T < 0) return ENERGON_ERR_SHAPE;
+  if ((int64_t)max_len * 3 * cfg->n_heads * cfg->head_dim * esize(cfg->dtype) >= ((int64_t)1 << 32)) return ENERGON_ERR_UNSUPPORTED;
+  int64_t total = 0;
+  st = check_lengths(lengths, B, max_len, &total);
+  if (st != ENERGON_OK) return st;
+  if (total != T) return ENERGON_ERR_LENGTH;
+  if (T >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
+  const void* ptrs[] = {x, y, ws, w->wf_qkv, w->c_qkv, w->bf_qkv, w->w_o, w->b_o, w->wf_fc1, w->c_fc1, w->bf_fc1,
+                        w->w_fc2, w->b_fc2};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ENERGON_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return ENERGON_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(stats_in) & 7u) || (reinterpret_cast<uintptr_t>(stats_out) & 7u)) return ENERGON_ERR_ALIGN;
+  if (ws_bytes < ws_layout(cfg, T).total) return ENERGON_ERR_CAPACITY;
+  return layer_folded_impl(cfg, w, x, y, T, cu, B, max_len, ws, stats_in, stats_out, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

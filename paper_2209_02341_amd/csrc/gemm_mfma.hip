@@ -72,21 +72,28 @@ __device__ __forceinline__ bool tile_origin(int32_t tiles_m, int32_t tiles_n, in
 template <typename E, int TM, int TN>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const E* __restrict__ bias,
                                            const E* res, E* y, int64_t M, int32_t N, int epi, int64_t mw,
-                                           int32_t nw, int lane) {
+                                           int32_t nw, int lane, const LnFold& lf) {
   const int lrow = lane & 31, lhalf = lane >> 5;
+  const bool fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int32_t n = nw + j * 32 + lrow;
     const bool n_ok = n < N;
-    const float bv = (bias != nullptr && n_ok) ? static_cast<float>(bias[n]) : 0.f;
+    const float bv = !n_ok ? 0.f : fold ? lf.bias[n] : bias != nullptr ? static_cast<float>(bias[n]) : 0.f;
+    const float cv = (fold && n_ok) ? lf.colsum[n] : 0.f;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int64_t m = mw + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
         if (n_ok && m < M) {
-          float v = acc[i][j][e] + bv;
-          if (epi == EPI_BIAS_GELU) v = gelu_erf(v);
+          float v = acc[i][j][e];
+          if (fold) {
+            const float2 st = *reinterpret_cast<const float2*>(lf.stats + 2 * m);
+            v = st.y * (v - st.x * cv);
+          }
+          v += bv;
+          if (epi == EPI_BIAS_GELU || epi == EPI_LNFOLD_GELU) v = gelu_erf(v);
           if (epi == EPI_BIAS_RESIDUAL) v += static_cast<float>(res[(size_t)m * N + n]);
           y[(size_t)m * N + n] = static_cast<E>(v);
         }
@@ -105,14 +112,33 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const E*
 // x / W slabs out of the L2 (measured: 1.4 % faster).
 constexpr int kEpiLd = 132;
 constexpr int kEpiWaveFloats = 64 * kEpiLd;
+
+// Sum over the 16 lanes of a DPP row (lanes 16 k .. 16 k + 15), left in every one of them:
+// neighbour, other pair of the quad, other quad of the half row, other half row.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x140, 0xF, 0xF, true));  // row_mirror
+  return v;
+}
+
 template <typename E>
 __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], const E* __restrict__ bias,
                                                      const E* res, E* y, int32_t N, int epi, int64_t mw,
-                                                     int32_t nw, int lane, float* stage) {
+                                                     int32_t nw, int lane, float* stage, const LnFold& lf) {
   const int lrow = lane & 15, lq = lane >> 4;
   const int rr = lane >> 4, c8 = (lane & 15) * 8;
-  float bv[8];
-  if (bias != nullptr) {
+  const bool fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
+  float bv[8], cv[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) cv[q] = 0.f;
+  if (fold) {
+    const float4 b0 = *reinterpret_cast<const float4*>(lf.bias + nw + c8), b1 = *reinterpret_cast<const float4*>(lf.bias + nw + c8 + 4);
+    const float4 c0 = *reinterpret_cast<const float4*>(lf.colsum + nw + c8), c1 = *reinterpret_cast<const float4*>(lf.colsum + nw + c8 + 4);
+    bv[0] = b0.x; bv[1] = b0.y; bv[2] = b0.z; bv[3] = b0.w; bv[4] = b1.x; bv[5] = b1.y; bv[6] = b1.z; bv[7] = b1.w;
+    cv[0] = c0.x; cv[1] = c0.y; cv[2] = c0.z; cv[3] = c0.w; cv[4] = c1.x; cv[5] = c1.y; cv[6] = c1.z; cv[7] = c1.w;
+  } else if (bias != nullptr) {
     const vec8<E> b8 = *reinterpret_cast<const vec8<E>*>(bias + nw + c8);
 #pragma unroll
     for (int q = 0; q < 8; ++q) bv[q] = static_cast<float>(b8[q]);
@@ -122,6 +148,21 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
   }
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
+    // What the rows of this pass need from global memory (residual segments, row statistics) is
+    // requested before the staging, so that its latency passes behind the barriers and the LDS
+    // traffic instead of stalling every row of the loop below.
+    vec8<E> rpre[16];
+    float2 spre[16];
+    if (epi == EPI_BIAS_RESIDUAL) {
+#pragma unroll
+      for (int it = 0; it < 16; ++it)
+        rpre[it] = *reinterpret_cast<const vec8<E>*>(res + (size_t)(mw + pass * 64 + it * 4 + rr) * N + nw + c8);
+    }
+    if (fold) {
+#pragma unroll
+      for (int it = 0; it < 16; ++it)
+        spre[it] = *reinterpret_cast<const float2*>(lf.stats + 2 * (mw + pass * 64 + it * 4 + rr));
+    }
     __syncthreads();  // the slab buffers (first pass) / the previous pass's rows are no longer read
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
@@ -131,28 +172,47 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
         for (int e = 0; e < 4; ++e)
           stage[(ii * 16 + lq * 4 + e) * kEpiLd + j * 16 + lrow] = acc[pass * 4 + ii][j][e];
     __syncthreads();
-#pragma unroll 4
+#pragma unroll
     for (int it = 0; it < 16; ++it) {
       const int r = it * 4 + rr;
       const float4 lo = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8]);
       const float4 hi = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8 + 4]);
       float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       const size_t off = (size_t)(mw + pass * 64 + r) * N + nw + c8;
+      if (fold) {  // r (v - mu c) + b as two multiply-adds
+        const float rmu = spre[it].y * spre[it].x;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] += bv[q];
-      if (epi == EPI_BIAS_GELU) {
+        for (int q = 0; q < 8; ++q) v[q] = fmaf(spre[it].y, v[q], fmaf(-rmu, cv[q], bv[q]));
+      } else {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] += bv[q];
+      }
+      if (epi == EPI_BIAS_GELU || epi == EPI_LNFOLD_GELU) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] = gelu_erf(v[q]);
       }
       if (epi == EPI_BIAS_RESIDUAL) {
-        const vec8<E> r8 = *reinterpret_cast<const vec8<E>*>(res + off);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] += static_cast<float>(r8[q]);
+        for (int q = 0; q < 8; ++q) v[q] += static_cast<float>(rpre[it][q]);
       }
       vec8<E> o;
 #pragma unroll
       for (int q = 0; q < 8; ++q) o[q] = static_cast<E>(v[q]);
       __builtin_nontemporal_store(o, reinterpret_cast<vec8<E>*>(y + off));
+      if (lf.partial != nullptr) {  // the 16 lanes of this row hold one 128-column segment of it
+        float s1 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s1 += static_cast<float>(o[q]);
+        s1 = row16_sum(s1);
+        const float seg_mean = s1 * (1.0f / kStatSeg);
+        float s2 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { const float d = static_cast<float>(o[q]) - seg_mean; s2 += d * d; }
+        s2 = row16_sum(s2);
+        if ((lane & 15) == 0)
+          *reinterpret_cast<float2*>(lf.partial + ((size_t)(mw + pass * 64 + r) * (N / kStatSeg) + nw / kStatSeg) * 2) =
+              make_float2(s1, s2);
+      }
     }
   }
 }
@@ -164,7 +224,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
                                                                      const E* __restrict__ bias,
                                                                      const E* res, E* y, int64_t M,
                                                                      int32_t N, int32_t K, int epi, int32_t tiles_m,
-                                                                     int32_t tiles_n) {
+                                                                     int32_t tiles_n, LnFold lf) {
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -271,7 +331,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
     __syncthreads();
   }
 
-  store_tile<E, TM, TN>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane);
+  store_tile<E, TM, TN>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane, lf);
 }
 
 // ---- hand-scheduled 256x256 kernel ----------------------------------------------------------
@@ -307,7 +367,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
                                                                     const E* __restrict__ bias,
                                                                     const E* res, E* y, int64_t M,
                                                                     int32_t N, int32_t K, int epi, int32_t tiles_m,
-                                                                    int32_t tiles_n) {
+                                                                    int32_t tiles_n, LnFold lf) {
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 16, TN = WTN / 16;
@@ -499,14 +559,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   int lane_e = lane;
   asm volatile("" : "+v"(lane_e));
   store_tile_coalesced(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
-                       reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats);
+                       reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf);
   ENERGON_STAMP(3);
 }
 
 template <typename E, typename Kern>
 static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int threads, size_t lds, const E* x,
                                const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
-                               int32_t K, int epi, hipStream_t s) {
+                               int32_t K, int epi, const LnFold& lf, hipStream_t s) {
   if (!attr_set) {  // idempotent; a race between host threads only repeats the call
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -516,39 +576,54 @@ static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int th
   const int32_t tiles_m = (int32_t)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
   const int64_t total = (int64_t)tiles_m * tiles_n;
   const int64_t grid = (total + kXcds - 1) / kXcds * kXcds;
-  kern<<<dim3((unsigned)grid), dim3(threads), lds, s>>>(x, w, bias, res, y, M, N, K, epi, tiles_m, tiles_n);
+  kern<<<dim3((unsigned)grid), dim3(threads), lds, s>>>(x, w, bias, res, y, M, N, K, epi, tiles_m, tiles_n, lf);
   return hipGetLastError();
+}
+
+// The 256x256 kernel needs whole tiles to shift at the edges, an even number of slabs, and enough
+// tiles for most of the 256 CUs.  Shifted edge tiles overlap their neighbours: with the residual
+// aliasing y, an overlapped element could be read after the neighbour's write, so that case
+// needs whole tiles.
+static bool takes_sched_kernel(int64_t M, int32_t N, int32_t K, bool res_aliases_y) {
+  const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  const bool overlap_safe = !res_aliases_y || (M % 256 == 0 && N % 256 == 0);
+  return M >= 256 && N >= 256 && K % 128 == 0 && big_tiles >= 192 && overlap_safe;
+}
+
+// Row partials come from the 256x256 kernel's epilogue, one per 128-column segment, and a
+// shifted column tile would count its overlap twice: whole column tiles only.
+bool gemm_emits_row_partials(int64_t M, int32_t N, int32_t K, bool res_aliases_y) {
+  return takes_sched_kernel(M, N, K, res_aliases_y) && N % 256 == 0;
 }
 
 template <typename E>
 static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
-                                   int32_t K, int epi, hipStream_t s) {
+                                   int32_t K, int epi, hipStream_t s, const LnFold* fold) {
   if (M <= 0) return hipSuccess;
   static bool attr_big = false, attr_small = false;  // per element type
-  const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  // the 256x256 kernel needs whole tiles to shift at the edges, an even number of slabs, and
-  // enough tiles for most of the 256 CUs
-  // (shifted edge tiles overlap their neighbours: with the residual aliasing y, an overlapped
-  // element could be read after the neighbour's write, so that case needs whole tiles)
-  const bool overlap_safe = res != y || (M % 256 == 0 && N % 256 == 0);
-  if (M >= 256 && N >= 256 && K % 128 == 0 && big_tiles >= 192 && overlap_safe) {
+  const LnFold lf = fold != nullptr ? *fold : LnFold{};
+  const bool wants_fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
+  if (wants_fold && (lf.stats == nullptr || lf.colsum == nullptr || lf.bias == nullptr)) return hipErrorInvalidValue;
+  if (lf.partial != nullptr && (epi != EPI_BIAS_RESIDUAL || !gemm_emits_row_partials(M, N, K, res == y)))
+    return hipErrorInvalidValue;
+  if (takes_sched_kernel(M, N, K, res == y)) {
     constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
     constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
     return launch_tiles<E>(gemm_mfma_sched_kernel<E, 256, 256, 2, 2>, attr_big, 256, 256, 256,
-                           slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, s);
+                           slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, lf, s);
   }
   return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2>, attr_small, 128, 128, 256,
-                         2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, s);
+                         2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
-                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s) {
-  return launch_gemm_mfma<bf16_t>(x, w, bias, res, y, M, N, K, epi, s);
+                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold) {
+  return launch_gemm_mfma<bf16_t>(x, w, bias, res, y, M, N, K, epi, s, fold);
 }
 
 hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y, int64_t M,
-                           int32_t N, int32_t K, int epi, hipStream_t s) {
-  return launch_gemm_mfma<f16_t>(x, w, bias, res, y, M, N, K, epi, s);
+                           int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold) {
+  return launch_gemm_mfma<f16_t>(x, w, bias, res, y, M, N, K, epi, s, fold);
 }
 
 }  // namespace energon

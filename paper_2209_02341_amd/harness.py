@@ -41,6 +41,24 @@ class DeviceLayer:
         self.struct = E.make_weights(self.tensors)
 
 
+class FoldedDeviceLayer:
+    """A DeviceLayer with both LayerNorms folded into the linears that follow them, by the
+    library's own fold kernel; the struct is what energon_layer_forward_ln_folded takes."""
+
+    def __init__(self, layer: DeviceLayer):
+        t = layer.tensors
+        self.tensors = {k: t.get(k) for k in ("w_o", "b_o", "w_fc2", "b_fc2")}
+        for name, w, b, g, beta in (("qkv", "w_qkv", "b_qkv", "ln1_g", "ln1_b"),
+                                    ("fc1", "w_fc1", "b_fc1", "ln2_g", "ln2_b")):
+            N = t[w].shape[0]
+            wf = torch.empty_like(t[w])
+            c = torch.empty(N, dtype=torch.float32, device=wf.device)
+            bf = torch.empty(N, dtype=torch.float32, device=wf.device)
+            E.energon_fold_layernorm(t[w], t.get(b), t[g], t[beta], wf, c, bf)
+            self.tensors["wf_" + name], self.tensors["c_" + name], self.tensors["bf_" + name] = wf, c, bf
+        self.struct = E.make_folded_weights(self.tensors)
+
+
 class PackedRun:
     """Buffers for one batch: packed activations (ping/pong), cu_seqlens, token_idx, workspace."""
 
@@ -64,6 +82,24 @@ class PackedRun:
         src, dst = self.x_packed, self.y_packed
         for layer in layers:
             E.energon_layer_forward(cfg, layer.struct, src, dst, T, self.cu, lengths, self.S, self.workspace)
+            src, dst = dst, src
+        self.last_packed = src
+        E.energon_unpack(src, self.cu, T, self.y_padded)
+        return self.y_padded
+
+    def forward_folded(self, x_padded: torch.Tensor, lengths: np.ndarray, layers: list) -> torch.Tensor:
+        """forward() on FoldedDeviceLayers: the first layer takes its row statistics itself, every
+        later one gets them from the epilogue of the layer before."""
+        cfg = self.cfg
+        self.T = T = E.energon_pack(x_padded, lengths, self.x_packed, self.cu, self.idx)
+        if not hasattr(self, "stats"):
+            cap = self.x_packed.shape[0]
+            self.stats = [torch.empty((cap, 2), dtype=torch.float32, device=self.x_packed.device) for _ in range(2)]
+        src, dst = self.x_packed, self.y_packed
+        for i, layer in enumerate(layers):
+            E.energon_layer_forward_ln_folded(cfg, layer.struct, src, dst, T, self.cu, lengths, self.S,
+                                              self.workspace, stats_in=self.stats[i & 1] if i else None,
+                                              stats_out=self.stats[(i + 1) & 1] if i + 1 < len(layers) else None)
             src, dst = dst, src
         self.last_packed = src
         E.energon_unpack(src, self.cu, T, self.y_padded)

@@ -150,3 +150,46 @@ def test_padded_attention_path_entry_points_reject_bad_arguments():
     assert f(*args, None, 1 << 30, None, None) == -1
     assert f(*args, FAKE, 16, None, None) == -4
     assert f(*args, FAKE + 16, 1 << 30, None, None) == -5
+
+
+def test_ln_folded_entry_points_reject_bad_arguments():
+    l = E.lib()
+    f = l.energon_fold_layernorm
+    assert f(FAKE, None, FAKE, FAKE, 8, 64, E.BF16, FAKE + 256, None, FAKE, None) == -1
+    assert f(FAKE, None, FAKE, FAKE, 8, 64, E.F32, FAKE + 256, FAKE, FAKE, None) == -6
+    assert f(FAKE, None, FAKE, FAKE, 8, 60, E.BF16, FAKE + 256, FAKE, FAKE, None) == -2
+    assert f(FAKE, None, FAKE, FAKE, 8, 64, E.BF16, FAKE, FAKE, FAKE, None) == -6          # in place
+    assert f(FAKE, None, FAKE, FAKE, 8, 64, E.BF16, FAKE + 256, FAKE + 4, FAKE, None) == -5
+    s = l.energon_row_stats
+    assert s(FAKE, 4, 64, E.BF16, 1e-5, None, None) == -1
+    assert s(FAKE, 4, 64, E.F32, 1e-5, FAKE, None) == -6
+    assert s(FAKE, 4, 60, E.BF16, 1e-5, FAKE, None) == -2
+    assert s(FAKE, 4, 1 << 16, E.BF16, 1e-5, FAKE, None) == -6
+    assert s(FAKE, 4, 64, E.BF16, -1.0, FAKE, None) == -2
+    assert s(FAKE, 0, 64, E.BF16, 1e-5, FAKE, None) == 0                                   # M = 0: nothing to do
+    g = l.energon_linear_ln_folded
+    assert g(FAKE, FAKE, FAKE, FAKE, None, FAKE, 4, 64, 64, 0, E.BF16, None) == -1
+    assert g(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, 64, 96, 0, E.BF16, None) == -2
+    assert g(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, 64, 64, 0, E.F32, None) == -6
+    assert g(FAKE, FAKE, FAKE + 4, FAKE, FAKE, FAKE, 4, 64, 64, 0, E.BF16, None) == -5
+    assert E.energon_stats_scratch_bytes(1000, 5120) == 1000 * 40 * 8
+    assert E.energon_stats_scratch_bytes(3, 200) == 256
+    assert E.energon_stats_scratch_bytes(-1, 64) == 0
+    r = l.energon_linear_residual_stats
+    assert r(FAKE, FAKE, None, None, FAKE, 4, 64, 64, E.BF16, 1e-5, FAKE, FAKE, 1 << 20, None) == -1
+    assert r(FAKE, FAKE, None, FAKE, FAKE, 4, 64, 64, E.BF16, 1e-5, FAKE, FAKE, 16, None) == -4
+    assert r(FAKE, FAKE, None, FAKE, FAKE, 4, 64, 64, E.BF16, 1e-5, FAKE, FAKE + 16, 1 << 20, None) == -5
+    assert r(FAKE, FAKE, None, FAKE, FAKE, 4, 1 << 16, 64, E.BF16, 1e-5, FAKE, FAKE, 1 << 30, None) == -6
+    c = cfg()
+    w = E.FoldedLayerWeights(*([FAKE] * 10))
+    lens = np.asarray([3, 2], dtype=np.int32)
+    lf = l.energon_layer_forward_ln_folded
+    assert lf(C.byref(c), C.byref(w), FAKE, FAKE, 5, FAKE, lens.ctypes.data, 2, 4, FAKE, 16, None, None, None) == -4
+    assert lf(C.byref(c), C.byref(w), FAKE, FAKE, 6, FAKE, lens.ctypes.data, 2, 4, FAKE, 1 << 30, None, None, None) == -3
+    assert lf(C.byref(c), C.byref(w), FAKE, FAKE, 5, FAKE, lens.ctypes.data, 2, 4, FAKE, 1 << 30, FAKE + 4, None, None) == -5
+    w.c_fc1 = None
+    assert lf(C.byref(c), C.byref(w), FAKE, FAKE, 5, FAKE, lens.ctypes.data, 2, 4, FAKE, 1 << 30, None, None, None) == -1
+    c32 = cfg()
+    c32.dtype = E.F32
+    w = E.FoldedLayerWeights(*([FAKE] * 10))
+    assert lf(C.byref(c32), C.byref(w), FAKE, FAKE, 5, FAKE, lens.ctypes.data, 2, 4, FAKE, 1 << 30, None, None, None) == -6

@@ -1,0 +1,212 @@
+"""GPU parity for LayerNorm folded into the following linear (the fusion Sec. 5.5 of the paper
+attributes to the comparison system), through the C ABI against the CPU fp64 oracle.
+
+The result's definition stays linear(layer_norm(x), W, b) of the oracle; the pieces the fused
+kernels exchange (folded weights, column sums, folded bias, row statistics) are compared with the
+oracle's statements of them.  Tolerances as for the unfused path (bf16 1e-2, fp16 2.5e-3 of the
+tensor's scale); fp32 side arrays: 1e-5 relative (fp32 sums of a few thousand terms); the folded
+weight itself is one rounding of an fp32 product, compared at the storage type's half-ulp.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import energon_oracle as orc
+from paper_2209_02341_amd import binding as E
+from paper_2209_02341_amd import harness as hz
+from paper_2209_02341_amd import workloads as wl
+from test_gpu_parity import TOL, assert_close
+
+pytestmark = pytest.mark.gpu
+
+EPS = 1e-5
+
+
+def f32(n):
+    return torch.empty(n, dtype=torch.float32, device="cuda")
+
+
+def fold_on_gpu(w, b, g, beta, dtype):
+    wd, bd, gd, betad = (hz.to_device(a, dtype) for a in (w, b, g, beta))
+    wf = torch.empty_like(wd)
+    c, bf = f32(w.shape[0]), f32(w.shape[0])
+    E.energon_fold_layernorm(wd, bd, gd, betad, wf, c, bf)
+    return wf, c, bf
+
+
+@pytest.mark.parametrize("N,K,dtype", [(264, 192, wl.BF16), (7, 64, wl.BF16), (1024, 5120, wl.BF16), (130, 256, wl.F16)])
+def test_fold_weights(N, K, dtype):
+    rng = np.random.default_rng(N + K)
+    w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
+    b = wl.round_to_dtype(rng.standard_normal(N) * 0.5, dtype)
+    g = wl.round_to_dtype(1.0 + 0.3 * rng.standard_normal(K), dtype)
+    beta = wl.round_to_dtype(0.5 * rng.standard_normal(K), dtype)
+    for bias in (b, None):
+        wf, c, bf = fold_on_gpu(w, bias, g, beta, dtype)
+        # the rounding decision is taken in the kernel's precision (an fp32 product, exact for two
+        # 16-bit factors, rounded once to the storage type): same rule on this side -> bit-exact
+        want_wf = wl.round_to_dtype(w.astype(np.float64) * g.astype(np.float64), dtype)
+        got_wf = hz.to_host(wf)
+        assert np.array_equal(got_wf, want_wf.astype(np.float64)), "folded weights are not the rounded products"
+        _, c_ref, bf_ref = orc.fold_layer_norm(w.astype(np.float64), None if bias is None else bias.astype(np.float64),
+                                               g.astype(np.float64), beta.astype(np.float64),
+                                               round_weights=lambda a: wl.round_to_dtype(a, dtype).astype(np.float64))
+        scale_c = np.abs(want_wf).sum(axis=1).max()
+        assert np.abs(c.cpu().numpy() - c_ref).max() <= 1e-5 * scale_c
+        scale_b = (np.abs(w) @ np.abs(beta)).max() + np.abs(b).max()
+        assert np.abs(bf.cpu().numpy() - bf_ref).max() <= 1e-5 * scale_b
+
+
+@pytest.mark.parametrize("M,K,dtype", [(37, 64, wl.BF16), (300, 1024, wl.BF16), (64, 5120, wl.BF16), (5, 12288, wl.BF16),
+                                       (3, 32768, wl.BF16), (129, 264, wl.F16)])
+def test_row_stats(M, K, dtype):
+    rng = np.random.default_rng(M + K)
+    x = wl.round_to_dtype(rng.normal(2.0, 1.5, (M, K)), dtype)   # mean far from zero
+    x[0] = x[0, 0]                                               # a constant row: variance exactly 0
+    xd = hz.to_device(x, dtype)
+    st = torch.full((M + 1, 2), 7.0, dtype=torch.float32, device="cuda")
+    E.energon_row_stats(xd, EPS, st)
+    mu, r = orc.row_stats(x.astype(np.float64), EPS)
+    got = st.cpu().numpy().astype(np.float64)
+    assert np.abs(got[:M, 0] - mu).max() <= 1e-5 * np.abs(x).max()
+    assert np.abs(got[:M, 1] / r - 1).max() <= 1e-4
+    assert np.all(got[M] == 7.0), "row past M was written"
+
+
+FOLD_LINEAR_CASES = [
+    (300, 264, 192, wl.BF16), (1, 8, 64, wl.BF16), (515, 1024, 1024, wl.BF16),      # the predicated kernel
+    (3333, 3592, 256, wl.BF16), (3333, 3592, 384, wl.F16), (4096, 3072, 640, wl.BF16),  # the 256x256 kernel, ragged / whole
+]
+
+
+@pytest.mark.parametrize("M,N,K,dtype", FOLD_LINEAR_CASES)
+@pytest.mark.parametrize("gelu", [False, True])
+def test_linear_ln_folded_matches_layernorm_then_linear(M, N, K, dtype, gelu):
+    rng = np.random.default_rng(M + N + K + gelu)
+    x = wl.round_to_dtype(rng.normal(0.7, 1.3, (M, K)), dtype)
+    w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
+    b = wl.round_to_dtype(rng.standard_normal(N) * 0.5, dtype)
+    g = wl.round_to_dtype(1.0 + 0.2 * rng.standard_normal(K), dtype)
+    beta = wl.round_to_dtype(0.3 * rng.standard_normal(K), dtype)
+    wf, c, bf = fold_on_gpu(w, b, g, beta, dtype)
+    xd = hz.to_device(x, dtype)
+    st = f32((M, 2))
+    E.energon_row_stats(xd, EPS, st)
+    yd = torch.full((M + 1, N), 3.0, dtype=xd.dtype, device="cuda")
+    E.energon_linear_ln_folded(xd, wf, c, bf, st, yd, gelu)
+    ref = orc.linear(orc.layer_norm(x.astype(np.float64), g.astype(np.float64), beta.astype(np.float64), EPS),
+                     w.astype(np.float64), b.astype(np.float64))
+    if gelu:
+        ref = orc.gelu(ref)
+    out = hz.to_host(yd)
+    assert_close(out[:M], ref, dtype, f"folded linear gelu={gelu}")
+    assert np.all(out[M] == 3.0), "row past M was written"
+
+
+@pytest.mark.parametrize("M,N,K,dtype", [
+    (300, 264, 192, wl.BF16),        # predicated kernel: statistics by a pass over y
+    (3333, 3592, 128, wl.BF16),      # 256x256 kernel but a ragged column tile: pass over y
+    (3333, 3584, 256, wl.BF16),      # 256x256 kernel, whole column tiles, shifted row tile: epilogue partials
+    (4096, 5120, 128, wl.F16),       # whole tiles
+])
+def test_linear_residual_stats(M, N, K, dtype):
+    rng = np.random.default_rng(M + N + K)
+    x = wl.round_to_dtype(rng.standard_normal((M, K)), dtype)
+    w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
+    b = wl.round_to_dtype(rng.standard_normal(N) * 0.5, dtype)
+    r = wl.round_to_dtype(rng.normal(1.5, 1.0, (M, N)), dtype)
+    xd, wd, bd, rd = (hz.to_device(a, dtype) for a in (x, w, b, r))
+    yd = torch.empty((M, N), dtype=xd.dtype, device="cuda")
+    st = torch.full((M + 1, 2), 7.0, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(E.energon_stats_scratch_bytes(M, N), dtype=torch.uint8, device="cuda")
+    E.energon_linear_residual_stats(xd, wd, bd, rd, yd, EPS, st, scratch)
+    y = hz.to_host(yd)
+    assert_close(y, x.astype(np.float64) @ w.astype(np.float64).T + b + r, dtype, "residual linear")
+    # same bits as the plain entry point
+    y2 = torch.empty_like(yd)
+    E.energon_linear(xd, wd, bd, rd, y2, E.EPI_BIAS_RESIDUAL)
+    assert torch.equal(yd.view(torch.int16), y2.view(torch.int16))
+    # the statistics are those of the stored (rounded) y
+    mu, rs = orc.row_stats(y, EPS)
+    got = st.cpu().numpy().astype(np.float64)
+    assert np.abs(got[:M, 0] - mu).max() <= 1e-5 * np.abs(y).max()
+    assert np.abs(got[:M, 1] / rs - 1).max() <= 1e-4
+    assert np.all(got[M] == 7.0)
+    # and they are the same from run to run (fixed merge order)
+    st2 = torch.empty_like(st)
+    E.energon_linear_residual_stats(xd, wd, bd, rd, yd, EPS, st2, scratch)
+    assert torch.equal(st[:M], st2[:M])
+
+
+def run_folded(w, x, lens, layers):
+    cfg = hz.layer_config(w.hidden, w.n_heads, w.head_dim, w.ffn, w.dtype, w.ln_eps)
+    B, S, _ = x.shape
+    run = hz.PackedRun(cfg, B, S, int(lens.sum()))
+    dev = [hz.DeviceLayer(p, w.dtype) for p in layers]
+    folded = [hz.FoldedDeviceLayer(d) for d in dev]
+    y = run.forward_folded(hz.to_device(x, w.dtype), lens, folded)
+    torch.cuda.synchronize()
+    return run, y, dev
+
+
+@pytest.mark.parametrize("name", ["small_bf16", "small_f16"])
+def test_folded_layer_matches_oracle_with_intermediates(name):
+    w = wl.WORKLOADS[name]
+    lens, x, layers = wl.sample_lengths(w), wl.sample_x(w), [wl.sample_layer(w, 0)]
+    run, y, _ = run_folded(w, x, lens, layers)
+    st = {}
+    ref = orc.stack_forward(x, lens, layers, w.n_heads, w.head_dim, w.ln_eps, stages=st)
+    A = w.attn_width
+    for key, which, cols in (("qkv", E.WS_QKV, 3 * A), ("attn", E.WS_ATTN, A), ("y1", E.WS_Y1, w.hidden),
+                             ("m", E.WS_M, w.ffn)):
+        assert_close(hz.to_host(run.stage(which, cols)), orc.pack(st[key], lens), w.dtype, f"{name} folded stage {key}")
+    out = hz.to_host(y)
+    for b in range(w.batch):
+        assert np.all(out[b, lens[b]:] == 0)
+    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, f"{name} folded output")
+
+
+def test_folded_two_layer_stack_passes_statistics_on():
+    """Second layer takes its statistics from the first layer's last epilogue; lengths with an
+    empty sequence and a one-token sequence."""
+    w = wl.Workload("medium", wl.BF16, 2, 512, 4, 128, 1024, 5, 96, "uniform", 0, 96)
+    lens = np.array([96, 0, 33, 1, 70], dtype=np.int32)
+    x, layers = wl.sample_x(w), [wl.sample_layer(w, 0), wl.sample_layer(w, 1)]
+    _, y, _ = run_folded(w, x, lens, layers)
+    ref = orc.stack_forward(x, lens, layers, w.n_heads, w.head_dim, w.ln_eps)
+    out = hz.to_host(y)
+    assert np.all(out[1] == 0)
+    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, "folded two-layer stack")
+
+
+def test_folded_empty_batch_is_legal():
+    w = wl.Workload("empty", wl.BF16, 1, 128, 2, 64, 256, 3, 8, "uniform", 0, 0)
+    lens = np.zeros(3, dtype=np.int32)
+    _, y, _ = run_folded(w, wl.sample_x(w), lens, [wl.sample_layer(w, 0)])
+    assert torch.count_nonzero(y.float()).item() == 0
+
+
+@pytest.mark.timeout(600)
+def test_folded_full_size_13b_shape_sampled_sequences():
+    """The benchmark's workload at full size, 4 layers, on the launch shapes the benchmark times
+    (256x256 kernel, statistics from the epilogues): the oracle follows the two shortest
+    sequences through the stack; the result also stays close to the unfused path's."""
+    w = wl.WORKLOADS["gpt13b_bf16"]
+    lens, x = wl.sample_lengths(w), wl.sample_x(w)
+    layers = [wl.sample_layer(w, l) for l in range(w.layers)]
+    run, y, dev = run_folded(w, x, lens, layers)
+    picks = np.argsort(lens)[:2]
+    out = hz.to_host(y[torch.from_numpy(picks).cuda()])
+    sub_len = lens[picks]
+    s_sub = int(sub_len.max())
+    ref = orc.stack_forward(x[picks][:, :s_sub], sub_len, layers, w.n_heads, w.head_dim, w.ln_eps)
+    assert_close(orc.pack(out[:, :s_sub], sub_len), orc.pack(ref, sub_len), w.dtype, "13B-shape folded, sampled sequences")
+    y_folded = y.clone()
+    y_plain = run.forward(hz.to_device(x, w.dtype), lens, dev)
+    torch.cuda.synchronize()
+    a, b = hz.to_host(y_folded), hz.to_host(y_plain)
+    # each path is within TOL of the exact result, so the two may differ by twice that
+    assert_close(orc.pack(a, lens), orc.pack(b, lens), w.dtype, "folded vs unfused, whole batch", tol=2 * TOL[w.dtype])
+    yz = y_folded.float().abs().sum(dim=2).cpu().numpy()
+    for bb in range(w.batch):
+        assert np.all(yz[bb, lens[bb]:] == 0) and np.all(yz[bb, :lens[bb]] > 0)
