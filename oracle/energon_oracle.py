@@ -32,7 +32,9 @@ closed form, identity block with zero output weights, per-stage agreement with
 textbook library routines, and (for the paper's padded attention path) round trips,
 closed-form indices and agreement with the variable-length attention on valid tokens; for
 the LayerNorm-folded linear, the identity against layer_norm + linear, a hand-computed 2x2
-case and the rounding rule for its column sums.
+case and the rounding rule for its column sums; for the generation step, agreement with the
+last row of the whole-sequence forward at every position, the one-key closed form and a
+hand-computed two-key case; for the embedding and last-row gathers, closed-form indices.
 No function here is "parity unpinned".
 """
 import numpy as np
@@ -265,3 +267,68 @@ def stack_forward(x_pad, lengths, layer_params, n_heads, head_dim, eps=1e-5, sta
         st = stages if (stages is not None and li == len(layer_params) - 1) else None
         y = layer_forward_padded(y, lengths, p, n_heads, head_dim, eps, st)
     return zero_pad_rows(y, lengths)
+
+# ------------------------------------------------- one generation step on cached keys / values
+# The paper describes the decoder block (Sec. 2.2: causal mask) and its forward over a batch of
+# sequences of different lengths (Sec. 4.3), not token-by-token generation.  The step below is
+# what that definition implies: under a causal mask the rows of K and V that earlier tokens
+# produced never change, so the block's output for a token appended at position p is row p of the
+# block applied to the whole sequence, and it needs from the earlier tokens only their K and V
+# rows (the cache).  Each sequence of the batch has its own cache length: nothing is padded.
+def decode_attention(q_new, k_new, v_new, k_cache, v_cache, n_heads, head_dim):
+    """One sequence, one new token.  q_new, k_new, v_new [A]; k_cache, v_cache [p, A] (rows of the
+    p earlier tokens, p may be 0).  The query attends the p cached keys and its own key."""
+    A = n_heads * head_dim
+    keys = np.concatenate([k_cache.reshape(-1, A), k_new[None, :]], axis=0)
+    vals = np.concatenate([v_cache.reshape(-1, A), v_new[None, :]], axis=0)
+    out = np.empty(A, dtype=np.float64)
+    for h in range(n_heads):
+        sl = slice(h * head_dim, (h + 1) * head_dim)
+        s = keys[:, sl] @ q_new[sl] / np.sqrt(head_dim)
+        e = np.exp(s - s.max())
+        out[sl] = (e / e.sum()) @ vals[:, sl]
+    return out
+
+
+def decode_layer(x_new, caches, p, n_heads, head_dim, eps=1e-5):
+    """One pre-LN decoder block for one new token per sequence.  x_new [B, H]; caches[b] =
+    (k_cache [p_b, A], v_cache [p_b, A]).  Returns (y [B, H], k_new [B, A], v_new [B, A]); the
+    caller appends k_new[b], v_new[b] to sequence b's cache."""
+    x_new = np.asarray(x_new, dtype=np.float64)
+    f = lambda a: None if a is None else np.asarray(a, dtype=np.float64)
+    p = {k_: f(v_) for k_, v_ in p.items()}
+    A = n_heads * head_dim
+    u = layer_norm(x_new, p["ln1_g"], p["ln1_b"], eps)
+    qkv = linear(u, p["w_qkv"], p["b_qkv"])
+    q, k_new, v_new = qkv[:, 0:A], qkv[:, A:2 * A], qkv[:, 2 * A:3 * A]
+    attn = np.stack([decode_attention(q[b], k_new[b], v_new[b], np.asarray(caches[b][0], dtype=np.float64),
+                                      np.asarray(caches[b][1], dtype=np.float64), n_heads, head_dim)
+                     for b in range(x_new.shape[0])])
+    y1 = x_new + linear(attn, p["w_o"], p["b_o"])
+    w = layer_norm(y1, p["ln2_g"], p["ln2_b"], eps)
+    m = gelu(linear(w, p["w_fc1"], p["b_fc1"]))
+    return y1 + linear(m, p["w_fc2"], p["b_fc2"]), k_new, v_new
+
+
+# ------------------------------------------------------------- the two ends of the model
+def embed_packed(ids, lengths, wte, wpe):
+    """Token + position embedding on the packed layout: row t of the result belongs to position
+    t - cu[b] of its sequence b (Sec. 2.2 mentions the embedding layer only by name; learned
+    absolute positions as in the GPT models the paper runs)."""
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    out = np.empty((int(cu[-1]), wte.shape[1]), dtype=np.float64)
+    for b in range(len(lengths)):
+        for i in range(int(lengths[b])):
+            out[cu[b] + i] = wte[ids[cu[b] + i]] + wpe[i]
+    return out
+
+
+def last_token_rows(x_packed, lengths):
+    """Row of the last valid token of every sequence (what the next-token logits are computed
+    from); a sequence of length 0 gives a zero row."""
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    out = np.zeros((len(lengths), x_packed.shape[1]), dtype=np.float64)
+    for b in range(len(lengths)):
+        if lengths[b] > 0:
+            out[b] = x_packed[cu[b + 1] - 1]
+    return out
