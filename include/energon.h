@@ -290,6 +290,60 @@ int energon_layer_forward_ln_folded(const EnergonLayerConfig* cfg, const Energon
                                     int32_t max_len, void* workspace_dev, size_t workspace_bytes,
                                     const float* stats_in, float* stats_out, void* stream);
 
+/* ---- One generation step on cached keys / values (bf16 / fp16) --------------------------------
+ * The paper defines the decoder block with a causal mask (Sec. 2.2) and runs it over batches of
+ * sequences of different lengths without computing on padding (Sec. 4.3); it does not describe
+ * token-by-token generation.  Under a causal mask the K and V rows of earlier tokens never
+ * change, so the block's output for a token appended at position p is row p of the block applied
+ * to the whole sequence, and needs from the earlier tokens only their K and V rows.  These entry
+ * points compute that step for one new token per sequence; every sequence has its own cached
+ * length and nothing beyond it is read.
+ *
+ * Cache layout (per layer, device memory owned by the caller): k_cache, v_cache [B, S_cap, A]
+ * row-major, A = n_heads * head_dim, row p of sequence b = K / V of its token at position p.
+ * cache_lens_dev [B] int32 on the device: tokens already cached per sequence.  The caller advances
+ * it after the last layer of a step; the calls below only read it (so one array serves all layers
+ * and nothing is copied from the host: a sequence of these calls can be captured in a HIP graph).
+ * A length outside [0, S_cap] is clamped into it; at S_cap the new token still attends the whole
+ * cache but its K / V are not stored. */
+
+/* qkv [B, 3A] (q | k | v of the new tokens) -> out [B, A]; also writes row cache_lens[b] of both
+ * caches for every sequence.  head_dim 64 or 128. */
+int energon_decode_attention(const void* qkv, void* k_cache, void* v_cache, const int32_t* cache_lens_dev, int32_t B,
+                             int32_t S_cap, int32_t n_heads, int32_t head_dim, int32_t dtype, void* out,
+                             void* stream);
+
+/* Bytes of workspace for energon_decode_layer_forward with batch size B (0 if cfg is invalid). */
+size_t energon_decode_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B);
+
+/* One pre-LN decoder block for one new token per sequence: x [B, H] -> y [B, H] (may not alias),
+ * same weights and stage order as energon_layer_forward, the attention stage replaced by
+ * energon_decode_attention on this layer's caches.  With B <= 64 the four contractions run in a
+ * kernel that streams each weight matrix from HBM once.  cache_lens_host may be NULL; if given
+ * (a host copy of cache_lens_dev) every length is checked to be in [0, S_cap) before anything is
+ * launched (ENERGON_ERR_LENGTH).  workspace: energon_decode_workspace_bytes(cfg, B), 256-byte
+ * aligned.  B <= 65535. */
+int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* weights, const void* x,
+                                 void* y, int32_t B, const int32_t* cache_lens_dev, const int32_t* cache_lens_host,
+                                 void* k_cache, void* v_cache, int32_t S_cap, void* workspace_dev,
+                                 size_t workspace_bytes, void* stream);
+
+/* ---- The two ends of the model on the packed layout (bf16 / fp16) -----------------------------
+ * The paper names the embedding layer (Sec. 2.2) without describing it; learned absolute
+ * positions as in the GPT models it runs. */
+
+/* x_packed[t] = wte[ids[t]] + wpe[t - cu_seqlens[b]] for every packed row t of sequence b.
+ * ids_dev [T] int32, wte [V, H], wpe [P, H], H % 8 == 0.  Ids outside [0, V) and positions >= P
+ * are clamped into the tables. */
+int energon_embed_packed(const int32_t* ids_dev, const int32_t* cu_seqlens_dev, int64_t T, int32_t B, const void* wte,
+                         int32_t V, const void* wpe, int32_t P, int32_t H, int32_t dtype, void* x_packed,
+                         void* stream);
+
+/* out[b] = x_packed[cu_seqlens[b+1] - 1], the row of sequence b's last token (zeros if it is
+ * empty): what the next-token logits are computed from.  out [B, H]. */
+int energon_last_token_rows(const void* x_packed, const int32_t* cu_seqlens_dev, int32_t B, int32_t H, int32_t dtype,
+                            void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

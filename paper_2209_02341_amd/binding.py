@@ -86,6 +86,15 @@ def lib() -> C.CDLL:
         l.energon_linear_residual_stats.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, C.c_float, vp, vp, sz, vp]
         l.energon_layer_forward_ln_folded.argtypes = [pcfg, C.POINTER(FoldedLayerWeights), vp, vp, i64, vp, vp, i32,
                                                       i32, vp, sz, vp, vp, vp]
+        l.energon_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+        l.energon_decode_workspace_bytes.restype = sz
+        l.energon_decode_workspace_bytes.argtypes = [pcfg, i32]
+        l.energon_decode_layer_forward.argtypes = [pcfg, pw, vp, vp, i32, vp, vp, vp, vp, i32, vp, sz, vp]
+        l.energon_embed_packed.argtypes = [vp, vp, i64, i32, vp, i32, vp, i32, i32, i32, vp, vp]
+        l.energon_last_token_rows.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        for name in ("energon_decode_attention", "energon_decode_layer_forward", "energon_embed_packed",
+                     "energon_last_token_rows"):
+            getattr(l, name).restype = C.c_int
         for name in ("energon_fold_layernorm", "energon_row_stats", "energon_linear_ln_folded",
                      "energon_linear_residual_stats", "energon_layer_forward_ln_folded"):
             getattr(l, name).restype = C.c_int
@@ -314,3 +323,40 @@ def energon_layer_forward_ln_folded(cfg: LayerConfig, weights: FoldedLayerWeight
                                                  int(workspace.numel() * workspace.element_size()),
                                                  _ptr(stats_in), _ptr(stats_out), _stream(stream)),
            "energon_layer_forward_ln_folded")
+
+
+# ---- one generation step on cached keys / values; the two ends of the model
+def energon_decode_attention(qkv, k_cache, v_cache, cache_lens_dev, n_heads: int, head_dim: int, out,
+                             stream=None) -> None:
+    B, S_cap = k_cache.shape[0], k_cache.shape[1]
+    _check(lib().energon_decode_attention(_ptr(qkv), _ptr(k_cache), _ptr(v_cache), _ptr(cache_lens_dev), B, S_cap,
+                                          int(n_heads), int(head_dim), _dtype_code(qkv), _ptr(out), _stream(stream)),
+           "energon_decode_attention")
+
+
+def energon_decode_workspace_bytes(cfg: LayerConfig, B: int) -> int:
+    return int(lib().energon_decode_workspace_bytes(C.byref(cfg), int(B)))
+
+
+def energon_decode_layer_forward(cfg: LayerConfig, weights: LayerWeights, x, y, cache_lens_dev, cache_lens_host,
+                                 k_cache, v_cache, workspace, stream=None) -> None:
+    B, S_cap = k_cache.shape[0], k_cache.shape[1]
+    lens = None if cache_lens_host is None else _lengths(cache_lens_host)
+    _check(lib().energon_decode_layer_forward(C.byref(cfg), C.byref(weights), _ptr(x), _ptr(y), B,
+                                              _ptr(cache_lens_dev), _ptr(lens), _ptr(k_cache), _ptr(v_cache), S_cap,
+                                              _ptr(workspace), int(workspace.numel() * workspace.element_size()),
+                                              _stream(stream)), "energon_decode_layer_forward")
+
+
+def energon_embed_packed(ids_dev, cu_seqlens, wte, wpe, x_packed, stream=None) -> None:
+    T, H = x_packed.shape
+    B = cu_seqlens.shape[0] - 1
+    _check(lib().energon_embed_packed(_ptr(ids_dev), _ptr(cu_seqlens), T, B, _ptr(wte), wte.shape[0], _ptr(wpe),
+                                      wpe.shape[0], H, _dtype_code(wte), _ptr(x_packed), _stream(stream)),
+           "energon_embed_packed")
+
+
+def energon_last_token_rows(x_packed, cu_seqlens, out, stream=None) -> None:
+    B, H = out.shape
+    _check(lib().energon_last_token_rows(_ptr(x_packed), _ptr(cu_seqlens), B, H, _dtype_code(out), _ptr(out),
+                                         _stream(stream)), "energon_last_token_rows")

@@ -12,7 +12,8 @@ LIB = os.path.join(PKG, "libenergon.so")
 OBJ_DIR = os.path.join(os.path.dirname(PKG), "_build")
 
 SOURCES = ["energon_api.hip", "pack.hip", "layernorm.hip", "gemm_f32.hip", "gemm_mfma.hip",
-           "attention_f32.hip", "attention_mfma.hip", "drce.hip", "ln_fold.hip"]
+           "attention_f32.hip", "attention_mfma.hip", "drce.hip", "ln_fold.hip", "gemm_skinny.hip",
+           "decode_attention.hip", "model_ends.hip"]
 # packed-fp32 instructions are switched off for every device pass
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -130,6 +130,17 @@ hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias
                             int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
 hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y,
                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
+// gemm_skinny.hip: M <= 64 rows (a generation step), bound by streaming W once
+bool gemm_skinny_takes(int64_t M, int32_t N, int32_t K, int epi);
+template <typename E>
+hipError_t launch_gemm_skinny(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
+                              int32_t K, int epi, hipStream_t s);
+// decode_attention.hip, model_ends.hip (dtype 1 or 2 only)
+hipError_t launch_decode_attention(const void* qkv, void* k_cache, void* v_cache, const int32_t* lens, int32_t B,
+                                   int32_t S_cap, int32_t nh, int32_t d, int dtype, void* out, hipStream_t s);
+hipError_t launch_embed_packed(const int32_t* ids, const int32_t* cu, int32_t B, int64_t T, const void* wte, int32_t V,
+                               const void* wpe, int32_t P, int32_t H, int dtype, void* x, hipStream_t s);
+hipError_t launch_last_rows(const void* x, const int32_t* cu, int32_t B, int64_t row_bytes, void* out, hipStream_t s);
 // ln_fold.hip (dtype 1 or 2 only)
 hipError_t launch_fold_weights(const void* w, const void* b, const void* gamma, const void* beta, int32_t N, int32_t K,
                                int dtype, void* wf, float* colsum, float* bias_f, hipStream_t s);

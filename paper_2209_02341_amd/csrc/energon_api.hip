@@ -518,4 +518,96 @@ int energon_layer_forward_ln_folded(const EnergonLayerConfig* cfg, const Energon
   return layer_folded_impl(cfg, w, x, y, T, cu, B, max_len, ws, stats_in, stats_out, static_cast<hipStream_t>(stream));
 }
 
+int energon_decode_attention(const void* qkv, void* k_cache, void* v_cache, const int32_t* cache_lens_dev, int32_t B,
+                             int32_t S_cap, int32_t n_heads, int32_t head_dim, int32_t dtype, void* out,
+                             void* stream) {
+  if (!qkv || !k_cache || !v_cache || !cache_lens_dev || !out) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype) || (head_dim != 64 && head_dim != 128)) return ENERGON_ERR_UNSUPPORTED;
+  if (B < 0 || S_cap <= 0 || n_heads <= 0) return ENERGON_ERR_SHAPE;
+  if ((int64_t)B * n_heads >= ((int64_t)1 << 31)) return ENERGON_ERR_SHAPE;
+  if (!aligned16(qkv) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(cache_lens_dev) & 3u))
+    return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_decode_attention(qkv, k_cache, v_cache, cache_lens_dev, B, S_cap, n_heads, head_dim, dtype, out,
+                                  static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+size_t energon_decode_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B) {
+  if (check_cfg(cfg) != ENERGON_OK || B < 0) return 0;
+  const size_t t = ws_layout(cfg, B).total;
+  return t ? t : 256;
+}
+
+int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y,
+                                 int32_t B, const int32_t* cache_lens_dev, const int32_t* cache_lens_host,
+                                 void* k_cache, void* v_cache, int32_t S_cap, void* ws, size_t ws_bytes,
+                                 void* stream) {
+  int st = check_cfg(cfg);
+  if (st != ENERGON_OK) return st;
+  if (!is16(cfg->dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!w || !x || !y || !cache_lens_dev || !k_cache || !v_cache || !ws) return ENERGON_ERR_NULL;
+  if (!w->ln1_g || !w->ln1_b || !w->w_qkv || !w->w_o || !w->ln2_g || !w->ln2_b || !w->w_fc1 || !w->w_fc2)
+    return ENERGON_ERR_NULL;
+  if (B < 0 || B > 65535 || S_cap <= 0) return ENERGON_ERR_SHAPE;
+  if (x == y) return ENERGON_ERR_UNSUPPORTED;
+  if (cache_lens_host)
+    for (int32_t b = 0; b < B; ++b)
+      if (cache_lens_host[b] < 0 || cache_lens_host[b] >= S_cap) return ENERGON_ERR_LENGTH;
+  const void* ptrs[] = {x, y, ws, k_cache, v_cache, w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o, w->b_o,
+                        w->ln2_g, w->ln2_b, w->w_fc1, w->b_fc1, w->w_fc2, w->b_fc2};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return ENERGON_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || (reinterpret_cast<uintptr_t>(cache_lens_dev) & 3u))
+    return ENERGON_ERR_ALIGN;
+  if (ws_bytes < energon_decode_workspace_bytes(cfg, B)) return ENERGON_ERR_CAPACITY;
+  if (B == 0) return ENERGON_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const WsLayout l = ws_layout(cfg, B);
+  char* base = static_cast<char*>(ws);
+  void* u = base + l.off[ENERGON_WS_U];
+  void* qkv = base + l.off[ENERGON_WS_QKV];
+  void* att = base + l.off[ENERGON_WS_ATTN];
+  void* y1 = base + l.off[ENERGON_WS_Y1];
+  void* wn = base + l.off[ENERGON_WS_W];
+  void* m = base + l.off[ENERGON_WS_M];
+  const int32_t H = cfg->hidden, A = cfg->n_heads * cfg->head_dim, F = cfg->ffn, dt = cfg->dtype;
+#define STEP(call) do { st = (call); if (st != ENERGON_OK) return st; } while (0)
+  HIP_TRY(launch_layernorm(x, w->ln1_g, w->ln1_b, u, B, H, cfg->ln_eps, dt, s));
+  STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, B, 3 * A, H, ENERGON_EPI_BIAS, dt, s));
+  HIP_TRY(launch_decode_attention(qkv, k_cache, v_cache, cache_lens_dev, B, S_cap, cfg->n_heads, cfg->head_dim, dt,
+                                  att, s));
+  STEP(linear_impl(att, w->w_o, w->b_o, x, y1, B, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+  HIP_TRY(launch_layernorm(y1, w->ln2_g, w->ln2_b, wn, B, H, cfg->ln_eps, dt, s));
+  STEP(linear_impl(wn, w->w_fc1, w->b_fc1, nullptr, m, B, F, H, ENERGON_EPI_BIAS_GELU, dt, s));
+  STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, B, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+#undef STEP
+  return ENERGON_OK;
+}
+
+int energon_embed_packed(const int32_t* ids_dev, const int32_t* cu, int64_t T, int32_t B, const void* wte, int32_t V,
+                         const void* wpe, int32_t P, int32_t H, int32_t dtype, void* x_packed, void* stream) {
+  if (!ids_dev || !cu || !wte || !wpe || !x_packed) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (T < 0 || T >= ((int64_t)1 << 31) || B <= 0 || V <= 0 || P <= 0 || H <= 0 || H % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (!aligned16(wte) || !aligned16(wpe) || !aligned16(x_packed) || (reinterpret_cast<uintptr_t>(ids_dev) & 3u) ||
+      (reinterpret_cast<uintptr_t>(cu) & 3u))
+    return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_embed_packed(ids_dev, cu, B, T, wte, V, wpe, P, H, dtype, x_packed, static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_last_token_rows(const void* x_packed, const int32_t* cu, int32_t B, int32_t H, int32_t dtype, void* out,
+                            void* stream) {
+  if (!x_packed || !cu || !out) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (B < 0 || H <= 0 || H % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (!aligned16(x_packed) || !aligned16(out) || (reinterpret_cast<uintptr_t>(cu) & 3u)) return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_last_rows(x_packed, cu, B, (int64_t)H * esize(dtype), out, static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
 }  // extern "C"

@@ -606,6 +606,7 @@ static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const 
   if (wants_fold && (lf.stats == nullptr || lf.colsum == nullptr || lf.bias == nullptr)) return hipErrorInvalidValue;
   if (lf.partial != nullptr && (epi != EPI_BIAS_RESIDUAL || !gemm_emits_row_partials(M, N, K, res == y)))
     return hipErrorInvalidValue;
+  if (lf.partial == nullptr && gemm_skinny_takes(M, N, K, epi)) return launch_gemm_skinny<E>(x, w, bias, res, y, M, N, K, epi, s);
   if (takes_sched_kernel(M, N, K, res == y)) {
     constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
     constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);

@@ -193,3 +193,33 @@ def test_ln_folded_entry_points_reject_bad_arguments():
     c32.dtype = E.F32
     w = E.FoldedLayerWeights(*([FAKE] * 10))
     assert lf(C.byref(c32), C.byref(w), FAKE, FAKE, 5, FAKE, lens.ctypes.data, 2, 4, FAKE, 1 << 30, None, None, None) == -6
+
+
+def test_decode_and_model_end_entry_points_reject_bad_arguments():
+    l = E.lib()
+    a = l.energon_decode_attention
+    assert a(FAKE, FAKE, FAKE, None, 2, 8, 2, 64, E.BF16, FAKE, None) == -1
+    assert a(FAKE, FAKE, FAKE, FAKE, 2, 8, 2, 96, E.BF16, FAKE, None) == -6
+    assert a(FAKE, FAKE, FAKE, FAKE, 2, 8, 2, 64, E.F32, FAKE, None) == -6
+    assert a(FAKE, FAKE, FAKE, FAKE, 2, 0, 2, 64, E.BF16, FAKE, None) == -2
+    assert a(FAKE, FAKE, FAKE, FAKE + 2, 2, 8, 2, 64, E.BF16, FAKE, None) == -5
+    assert a(FAKE, FAKE, FAKE, FAKE, 0, 8, 2, 64, E.BF16, FAKE, None) == 0       # B = 0: nothing to do
+    c = cfg()
+    assert E.energon_decode_workspace_bytes(c, 4) == E.energon_workspace_bytes(c, 4)
+    w = E.LayerWeights(*([FAKE] * 12))
+    lens = np.asarray([3, 8], dtype=np.int32)
+    f = l.energon_decode_layer_forward
+    assert f(C.byref(c), C.byref(w), FAKE, FAKE + 256, 2, None, None, FAKE, FAKE, 8, FAKE, 1 << 30, None) == -1
+    assert f(C.byref(c), C.byref(w), FAKE, FAKE, 2, FAKE, None, FAKE, FAKE, 8, FAKE, 1 << 30, None) == -6   # x aliases y
+    assert f(C.byref(c), C.byref(w), FAKE, FAKE + 256, 2, FAKE, lens.ctypes.data, FAKE, FAKE, 8, FAKE, 1 << 30, None) == -3
+    assert f(C.byref(c), C.byref(w), FAKE, FAKE + 256, 2, FAKE, None, FAKE, FAKE, 8, FAKE, 16, None) == -4
+    assert f(C.byref(c), C.byref(w), FAKE, FAKE + 256, 2, FAKE, None, FAKE, FAKE, 0, FAKE, 1 << 30, None) == -2
+    e = l.energon_embed_packed
+    assert e(FAKE, FAKE, 5, 2, FAKE, 100, None, 16, 64, E.BF16, FAKE, None) == -1
+    assert e(FAKE, FAKE, 5, 2, FAKE, 100, FAKE, 16, 60, E.BF16, FAKE, None) == -2
+    assert e(FAKE, FAKE, 5, 2, FAKE, 100, FAKE, 16, 64, E.F32, FAKE, None) == -6
+    assert e(FAKE, FAKE, 0, 2, FAKE, 100, FAKE, 16, 64, E.BF16, FAKE, None) == 0
+    r = l.energon_last_token_rows
+    assert r(FAKE, None, 2, 64, E.BF16, FAKE, None) == -1
+    assert r(FAKE, FAKE, 2, 60, E.BF16, FAKE, None) == -2
+    assert r(FAKE, FAKE, 0, 64, E.BF16, FAKE, None) == 0
