@@ -130,11 +130,13 @@ hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias
                             int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
 hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y,
                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
-// gemm_skinny.hip: M <= 64 rows (a generation step), bound by streaming W once
+// gemm_skinny.hip: M <= 64 rows (a generation step), bound by streaming W once.  With `partial`
+// (gemm_skinny_partial_bytes bytes of scratch) K may be cut over several workgroups.
 bool gemm_skinny_takes(int64_t M, int32_t N, int32_t K, int epi);
+size_t gemm_skinny_partial_bytes(int64_t M, int32_t N, int32_t K);
 template <typename E>
 hipError_t launch_gemm_skinny(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
-                              int32_t K, int epi, hipStream_t s);
+                              int32_t K, int epi, hipStream_t s, float* partial = nullptr);
 // decode_attention.hip, model_ends.hip (dtype 1 or 2 only)
 hipError_t launch_decode_attention(const void* qkv, void* k_cache, void* v_cache, const int32_t* lens, int32_t B,
                                    int32_t S_cap, int32_t nh, int32_t d, int dtype, void* out, hipStream_t s);

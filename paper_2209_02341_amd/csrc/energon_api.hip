@@ -54,7 +54,18 @@ WsLayout ws_layout(const EnergonLayerConfig* c, int64_t T) {
 }
 
 int linear_impl(const void* x, const void* w, const void* bias, const void* res, void* y, int64_t M, int32_t N,
-                int32_t K, int32_t epi, int32_t dt, hipStream_t s, const LnFold* fold = nullptr) {
+                int32_t K, int32_t epi, int32_t dt, hipStream_t s, const LnFold* fold = nullptr,
+                float* skinny_partial = nullptr) {
+  if (skinny_partial != nullptr && is16(dt) && gemm_skinny_takes(M, N, K, epi)) {
+    // few rows and scratch for partial sums: K may be cut over several workgroups
+    if (dt == ENERGON_BF16)
+      HIP_TRY(launch_gemm_skinny<bf16_t>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, (const bf16_t*)res,
+                                         (bf16_t*)y, M, N, K, epi, s, skinny_partial));
+    else
+      HIP_TRY(launch_gemm_skinny<f16_t>((const f16_t*)x, (const f16_t*)w, (const f16_t*)bias, (const f16_t*)res,
+                                        (f16_t*)y, M, N, K, epi, s, skinny_partial));
+    return ENERGON_OK;
+  }
   if (dt == ENERGON_BF16)
     HIP_TRY(launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, (const bf16_t*)res, (bf16_t*)y,
                              M, N, K, epi, s, fold));
@@ -534,9 +545,22 @@ int energon_decode_attention(const void* qkv, void* k_cache, void* v_cache, cons
   return ENERGON_OK;
 }
 
+// scratch for the partial sums of the few-row contractions of a step (the largest of the four)
+static size_t decode_partial_bytes(const EnergonLayerConfig* c, int32_t B) {
+  if (!is16(c->dtype) || B < 1 || B > 64) return 0;
+  const int32_t H = c->hidden, A = c->n_heads * c->head_dim, F = c->ffn;
+  size_t m = 0;
+  const int32_t shapes[4][2] = {{3 * A, H}, {H, A}, {F, H}, {H, F}};
+  for (const auto& nk : shapes) {
+    const size_t b = gemm_skinny_takes(B, nk[0], nk[1], EPI_BIAS) ? gemm_skinny_partial_bytes(B, nk[0], nk[1]) : 0;
+    m = b > m ? b : m;
+  }
+  return round256(m);
+}
+
 size_t energon_decode_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B) {
   if (check_cfg(cfg) != ENERGON_OK || B < 0) return 0;
-  const size_t t = ws_layout(cfg, B).total;
+  const size_t t = ws_layout(cfg, B).total + decode_partial_bytes(cfg, B);
   return t ? t : 256;
 }
 
@@ -573,15 +597,16 @@ int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLay
   void* wn = base + l.off[ENERGON_WS_W];
   void* m = base + l.off[ENERGON_WS_M];
   const int32_t H = cfg->hidden, A = cfg->n_heads * cfg->head_dim, F = cfg->ffn, dt = cfg->dtype;
+  float* part = decode_partial_bytes(cfg, B) ? reinterpret_cast<float*>(base + l.total) : nullptr;
 #define STEP(call) do { st = (call); if (st != ENERGON_OK) return st; } while (0)
   HIP_TRY(launch_layernorm(x, w->ln1_g, w->ln1_b, u, B, H, cfg->ln_eps, dt, s));
-  STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, B, 3 * A, H, ENERGON_EPI_BIAS, dt, s));
+  STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, B, 3 * A, H, ENERGON_EPI_BIAS, dt, s, nullptr, part));
   HIP_TRY(launch_decode_attention(qkv, k_cache, v_cache, cache_lens_dev, B, S_cap, cfg->n_heads, cfg->head_dim, dt,
                                   att, s));
-  STEP(linear_impl(att, w->w_o, w->b_o, x, y1, B, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+  STEP(linear_impl(att, w->w_o, w->b_o, x, y1, B, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s, nullptr, part));
   HIP_TRY(launch_layernorm(y1, w->ln2_g, w->ln2_b, wn, B, H, cfg->ln_eps, dt, s));
-  STEP(linear_impl(wn, w->w_fc1, w->b_fc1, nullptr, m, B, F, H, ENERGON_EPI_BIAS_GELU, dt, s));
-  STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, B, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+  STEP(linear_impl(wn, w->w_fc1, w->b_fc1, nullptr, m, B, F, H, ENERGON_EPI_BIAS_GELU, dt, s, nullptr, part));
+  STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, B, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s, nullptr, part));
 #undef STEP
   return ENERGON_OK;
 }

@@ -205,7 +205,8 @@ def test_decode_and_model_end_entry_points_reject_bad_arguments():
     assert a(FAKE, FAKE, FAKE, FAKE + 2, 2, 8, 2, 64, E.BF16, FAKE, None) == -5
     assert a(FAKE, FAKE, FAKE, FAKE, 0, 8, 2, 64, E.BF16, FAKE, None) == 0       # B = 0: nothing to do
     c = cfg()
-    assert E.energon_decode_workspace_bytes(c, 4) == E.energon_workspace_bytes(c, 4)
+    assert E.energon_decode_workspace_bytes(c, 4) >= E.energon_workspace_bytes(c, 4)
+    assert E.energon_decode_workspace_bytes(c, 4) % 256 == 0
     w = E.LayerWeights(*([FAKE] * 12))
     lens = np.asarray([3, 8], dtype=np.int32)
     f = l.energon_decode_layer_forward

@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 # ------------------------------------------------------------------ few-row linear (M <= 64)
 SKINNY_CASES = [
     # M, N, K, dtype: every row-tile count (1, 2, 4), ragged M, K with fewer slabs than wavefronts
-    # (64, 192), an uneven split over the 8 wavefronts (640 = 10 slabs, 5120 = 80), one column block
+    # (64, 192), an uneven split over the 4 wavefronts (640 = 10 slabs, 576 = 9), one column block
     (1, 32, 64, wl.BF16), (7, 96, 192, wl.BF16), (16, 256, 640, wl.BF16), (17, 64, 1024, wl.BF16),
     (32, 1536, 5120, wl.BF16), (33, 128, 2048, wl.BF16), (64, 512, 4096, wl.BF16), (50, 320, 20480, wl.BF16),
     (5, 64, 576, wl.F16), (32, 256, 5120, wl.F16),
@@ -271,3 +271,30 @@ def test_embed_packed_and_last_rows(dtype):
     E.energon_last_token_rows(x[:T], cu, last[:len(lens)])
     assert np.array_equal(hz.to_host(last)[:len(lens)], orc.last_token_rows(got[:T], lens))
     assert np.all(hz.to_host(last)[len(lens)] == 3.0)
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F16])
+def test_decode_layer_with_split_contraction(dtype):
+    """A long FFN (10240 = 160 slabs) with few output columns: the FC2 contraction of the step is cut
+    over 4 workgroups along K and finished by the second kernel.  Also run-to-run identical."""
+    w = wl.Workload("dec_split", dtype, 1, 256, 4, 64, 10240, 5, 24, "uniform", 0, 24)
+    lens = np.array([0, 23, 7, 1, 12], dtype=np.int32)
+    rng = np.random.default_rng(21)
+    p = wl.sample_layer(w, 0)
+    A, B, S_cap = w.attn_width, 5, 24
+    kc = wl.round_to_dtype(rng.standard_normal((B, S_cap, A)), dtype)
+    vc = wl.round_to_dtype(rng.standard_normal((B, S_cap, A)), dtype)
+    x = wl.round_to_dtype(rng.standard_normal((B, w.hidden)), dtype)
+    cfg = hz.layer_config(w.hidden, w.n_heads, w.head_dim, w.ffn, dtype, w.ln_eps)
+    layer = hz.DeviceLayer(p, dtype)
+    ws = torch.empty(E.energon_decode_workspace_bytes(cfg, B), dtype=torch.uint8, device="cuda")
+    assert ws.numel() > E.energon_workspace_bytes(cfg, B), "no room for partial sums was planned"
+    outs = []
+    for _ in range(2):
+        xd, kd, vd = (hz.to_device(a, dtype) for a in (x, kc, vc))
+        y = torch.empty_like(xd)
+        E.energon_decode_layer_forward(cfg, layer.struct, xd, y, torch.tensor(lens, device="cuda"), lens, kd, vd, ws)
+        outs.append(y)
+    ref, _, _ = orc.decode_layer(x, [(kc[b, :lens[b]], vc[b, :lens[b]]) for b in range(B)], p, w.n_heads, w.head_dim, w.ln_eps)
+    assert_close(hz.to_host(outs[0]), ref, dtype, "step with a split FC2")
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
