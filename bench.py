@@ -12,6 +12,9 @@ the timed region.  Prints ONE JSON line:
   paper_attention_path  the layer with the attention stage done the paper's way (padded core
              between a rebuild-padding and a remove-padding transpose kernel)
   ln_folded  the same step with both LayerNorms folded into the contractions that follow them
+  decode     one generation step (one new token per sequence on cached keys / values of the
+             batch's lengths) through the same L layers: bound by streaming the weights and the
+             cache from HBM once; algorithmic bytes / time against the HBM peak
   cpu_baseline  the CPU oracle timed on a bounded sample of whole sequences, one layer
 """
 import argparse
@@ -43,6 +46,7 @@ def main():
     ap.add_argument("--no-padded", action="store_true")
     ap.add_argument("--no-paper-path", action="store_true")
     ap.add_argument("--no-ln-folded", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -192,6 +196,51 @@ def main():
             f"({ms_step / ms_f:.3f}x)")
         del folded_layers
 
+    # ---- one generation step on cached keys / values (HBM-bound): every sequence has as many cached
+    # tokens as it has valid tokens in the batch above; the lengths are not advanced between the
+    # timed steps, so every step does the same work ----
+    decode = None
+    if w.dtype != wl.F32 and not args.no_decode and B <= 64:
+        tdt = x_dev.dtype
+        s_cap = S + 8
+        kc = [torch.randn((B, s_cap, A), device="cuda", dtype=torch.float32).to(tdt) for _ in range(L)]
+        vc = [torch.randn((B, s_cap, A), device="cuda", dtype=torch.float32).to(tdt) for _ in range(L)]
+        x_new = x_dev[:, 0].contiguous()
+        bufs = [torch.empty_like(x_new) for _ in range(2)]
+        lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        dws = torch.empty(E.energon_decode_workspace_bytes(cfg, B), dtype=torch.uint8, device="cuda")
+
+        def decode_step():
+            src = x_new
+            for i, layer in enumerate(dev_layers):
+                E.energon_decode_layer_forward(cfg, layer.struct, src, bufs[i & 1], lens_d, lens if i == 0 else None,
+                                               kc[i], vc[i], dws)
+                src = bufs[i & 1]
+
+        for _ in range(3):
+            decode_step()
+        n_dec = max(5, args.steps)
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        d0.record()
+        for _ in range(n_dec):
+            decode_step()
+        d1.record()
+        torch.cuda.synchronize()
+        ms_dec = d0.elapsed_time(d1) / n_dec
+        weight_bytes = esz * L * (3.0 * A * H + H * A + 2.0 * F * H)
+        kv_bytes = esz * L * 2.0 * A * float(lens.sum())
+        decode = {"ms_per_step": ms_dec, "value": B / (ms_dec * 1e-3), "unit": "generated tokens/s (batch of %d)" % B,
+                  "layers": L, "cached_tokens": int(lens.sum()),
+                  "roofline": {"bound": "hbm", "achieved": (weight_bytes + kv_bytes) / (ms_dec * 1e-3) / 1e9,
+                               "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": (weight_bytes + kv_bytes) / (ms_dec * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                               "algorithmic_bytes_per_step": weight_bytes + kv_bytes,
+                               "what": "weights read once + cached K and V rows read once"}}
+        log(f"[bench] generation step: {ms_dec * 1e3:.0f} us for {L} layers at batch {B} "
+            f"({decode['roofline']['achieved']:.0f} GB/s algorithmic, {B / (ms_dec * 1e-3):,.0f} tokens/s)")
+        del kc, vc, dws
+
     # ---- padded (no-elimination) path: same library, every position valid ----
     padded = None
     if not args.no_padded:
@@ -248,7 +297,7 @@ def main():
                      "flops_per_launch": gemm_flops_layer / 4},
         "stage_ms_per_layer": stage_ms, "stage_tflops": stage_tflops,
         "pack_ms": pack_ms, "unpack_ms": unpack_ms, "hbm": hbm,
-        "padded": padded, "paper_attention_path": paper_path, "ln_folded": ln_folded, "cpu_baseline": cpu,
+        "padded": padded, "paper_attention_path": paper_path, "ln_folded": ln_folded, "decode": decode, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 
