@@ -307,6 +307,13 @@ int energon_layer_forward_ln_folded(const EnergonLayerConfig* cfg, const Energon
  * A length outside [0, S_cap] is clamped into it; at S_cap the new token still attends the whole
  * cache but its K / V are not stored. */
 
+/* After a prefill: k_cache[b, i] = K row and v_cache[b, i] = V row of token i of sequence b, for
+ * every packed row of qkv_packed [T, 3A] (the ENERGON_WS_QKV stage that energon_layer_forward leaves
+ * in its workspace).  Positions >= S_cap are not stored; cache rows at and beyond a sequence's
+ * length are not touched.  A % 8 == 0. */
+int energon_cache_fill(const void* qkv_packed, const int32_t* cu_seqlens_dev, int64_t T, int32_t B, int32_t A,
+                       int32_t S_cap, int32_t dtype, void* k_cache, void* v_cache, void* stream);
+
 /* qkv [B, 3A] (q | k | v of the new tokens) -> out [B, A]; also writes row cache_lens[b] of both
  * caches for every sequence.  head_dim 64 or 128. */
 int energon_decode_attention(const void* qkv, void* k_cache, void* v_cache, const int32_t* cache_lens_dev, int32_t B,
@@ -338,6 +345,11 @@ int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLay
 int energon_embed_packed(const int32_t* ids_dev, const int32_t* cu_seqlens_dev, int64_t T, int32_t B, const void* wte,
                          int32_t V, const void* wpe, int32_t P, int32_t H, int32_t dtype, void* x_packed,
                          void* stream);
+
+/* x[i] = wte[ids[i]] + wpe[positions[i]] for n rows with explicit positions: the embedding of a
+ * generation step (positions_dev = the cached lengths).  Same clamping. */
+int energon_embed_at(const int32_t* ids_dev, const int32_t* positions_dev, int64_t n, const void* wte, int32_t V,
+                     const void* wpe, int32_t P, int32_t H, int32_t dtype, void* x, void* stream);
 
 /* out[b] = x_packed[cu_seqlens[b+1] - 1], the row of sequence b's last token (zeros if it is
  * empty): what the next-token logits are computed from.  out [B, H]. */

@@ -332,3 +332,17 @@ def last_token_rows(x_packed, lengths):
         if lengths[b] > 0:
             out[b] = x_packed[cu[b + 1] - 1]
     return out
+
+
+def cache_from_packed(qkv_packed, lengths, S_cap, A, fill=0.0):
+    """K and V of a prefill laid out as the generation step reads them: [B, S_cap, A] each, row i of
+    sequence b = columns A..2A / 2A..3A of its packed row cu[b] + i; other rows keep `fill`."""
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    B = len(lengths)
+    k = np.full((B, S_cap, A), fill, dtype=np.float64)
+    v = np.full((B, S_cap, A), fill, dtype=np.float64)
+    for b in range(B):
+        for i in range(min(int(lengths[b]), S_cap)):
+            k[b, i] = qkv_packed[cu[b] + i, A:2 * A]
+            v[b, i] = qkv_packed[cu[b] + i, 2 * A:3 * A]
+    return k, v

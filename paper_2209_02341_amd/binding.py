@@ -86,11 +86,15 @@ def lib() -> C.CDLL:
         l.energon_linear_residual_stats.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, C.c_float, vp, vp, sz, vp]
         l.energon_layer_forward_ln_folded.argtypes = [pcfg, C.POINTER(FoldedLayerWeights), vp, vp, i64, vp, vp, i32,
                                                       i32, vp, sz, vp, vp, vp]
+        l.energon_cache_fill.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp]
+        l.energon_cache_fill.restype = C.c_int
         l.energon_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
         l.energon_decode_workspace_bytes.restype = sz
         l.energon_decode_workspace_bytes.argtypes = [pcfg, i32]
         l.energon_decode_layer_forward.argtypes = [pcfg, pw, vp, vp, i32, vp, vp, vp, vp, i32, vp, sz, vp]
         l.energon_embed_packed.argtypes = [vp, vp, i64, i32, vp, i32, vp, i32, i32, i32, vp, vp]
+        l.energon_embed_at.argtypes = [vp, vp, i64, vp, i32, vp, i32, i32, i32, vp, vp]
+        l.energon_embed_at.restype = C.c_int
         l.energon_last_token_rows.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         for name in ("energon_decode_attention", "energon_decode_layer_forward", "energon_embed_packed",
                      "energon_last_token_rows"):
@@ -326,6 +330,13 @@ def energon_layer_forward_ln_folded(cfg: LayerConfig, weights: FoldedLayerWeight
 
 
 # ---- one generation step on cached keys / values; the two ends of the model
+def energon_cache_fill(qkv_packed, cu_seqlens, k_cache, v_cache, stream=None) -> None:
+    T = qkv_packed.shape[0]
+    B, S_cap, A = k_cache.shape
+    _check(lib().energon_cache_fill(_ptr(qkv_packed), _ptr(cu_seqlens), T, B, A, S_cap, _dtype_code(k_cache),
+                                    _ptr(k_cache), _ptr(v_cache), _stream(stream)), "energon_cache_fill")
+
+
 def energon_decode_attention(qkv, k_cache, v_cache, cache_lens_dev, n_heads: int, head_dim: int, out,
                              stream=None) -> None:
     B, S_cap = k_cache.shape[0], k_cache.shape[1]
@@ -354,6 +365,12 @@ def energon_embed_packed(ids_dev, cu_seqlens, wte, wpe, x_packed, stream=None) -
     _check(lib().energon_embed_packed(_ptr(ids_dev), _ptr(cu_seqlens), T, B, _ptr(wte), wte.shape[0], _ptr(wpe),
                                       wpe.shape[0], H, _dtype_code(wte), _ptr(x_packed), _stream(stream)),
            "energon_embed_packed")
+
+
+def energon_embed_at(ids_dev, positions_dev, wte, wpe, x, stream=None) -> None:
+    n, H = x.shape
+    _check(lib().energon_embed_at(_ptr(ids_dev), _ptr(positions_dev), n, _ptr(wte), wte.shape[0], _ptr(wpe),
+                                  wpe.shape[0], H, _dtype_code(wte), _ptr(x), _stream(stream)), "energon_embed_at")
 
 
 def energon_last_token_rows(x_packed, cu_seqlens, out, stream=None) -> None:

@@ -140,8 +140,11 @@ hipError_t launch_gemm_skinny(const E* x, const E* w, const E* bias, const E* re
 // decode_attention.hip, model_ends.hip (dtype 1 or 2 only)
 hipError_t launch_decode_attention(const void* qkv, void* k_cache, void* v_cache, const int32_t* lens, int32_t B,
                                    int32_t S_cap, int32_t nh, int32_t d, int dtype, void* out, hipStream_t s);
-hipError_t launch_embed_packed(const int32_t* ids, const int32_t* cu, int32_t B, int64_t T, const void* wte, int32_t V,
-                               const void* wpe, int32_t P, int32_t H, int dtype, void* x, hipStream_t s);
+hipError_t launch_embed_packed(const int32_t* ids, const int32_t* cu, const int32_t* positions, int32_t B, int64_t T,
+                               const void* wte, int32_t V, const void* wpe, int32_t P, int32_t H, int dtype, void* x,
+                               hipStream_t s);
+hipError_t launch_cache_fill(const void* qkv, const int32_t* cu, int32_t B, int64_t T, int64_t a_bytes, int32_t S_cap,
+                             void* kc, void* vc, hipStream_t s);
 hipError_t launch_last_rows(const void* x, const int32_t* cu, int32_t B, int64_t row_bytes, void* out, hipStream_t s);
 // ln_fold.hip (dtype 1 or 2 only)
 hipError_t launch_fold_weights(const void* w, const void* b, const void* gamma, const void* beta, int32_t N, int32_t K,

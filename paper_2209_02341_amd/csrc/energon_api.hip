@@ -558,6 +558,19 @@ static size_t decode_partial_bytes(const EnergonLayerConfig* c, int32_t B) {
   return round256(m);
 }
 
+int energon_cache_fill(const void* qkv_packed, const int32_t* cu, int64_t T, int32_t B, int32_t A, int32_t S_cap,
+                       int32_t dtype, void* k_cache, void* v_cache, void* stream) {
+  if (!cu || !k_cache || !v_cache || (!qkv_packed && T > 0)) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (T < 0 || T >= ((int64_t)1 << 31) || B <= 0 || A <= 0 || A % 8 != 0 || S_cap <= 0) return ENERGON_ERR_SHAPE;
+  if (!aligned16(qkv_packed) || !aligned16(k_cache) || !aligned16(v_cache) || (reinterpret_cast<uintptr_t>(cu) & 3u))
+    return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_cache_fill(qkv_packed, cu, B, T, (int64_t)A * esize(dtype), S_cap, k_cache, v_cache,
+                            static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
 size_t energon_decode_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B) {
   if (check_cfg(cfg) != ENERGON_OK || B < 0) return 0;
   const size_t t = ws_layout(cfg, B).total + decode_partial_bytes(cfg, B);
@@ -620,7 +633,22 @@ int energon_embed_packed(const int32_t* ids_dev, const int32_t* cu, int64_t T, i
   if (!aligned16(wte) || !aligned16(wpe) || !aligned16(x_packed) || (reinterpret_cast<uintptr_t>(ids_dev) & 3u) ||
       (reinterpret_cast<uintptr_t>(cu) & 3u))
     return ENERGON_ERR_ALIGN;
-  HIP_TRY(launch_embed_packed(ids_dev, cu, B, T, wte, V, wpe, P, H, dtype, x_packed, static_cast<hipStream_t>(stream)));
+  HIP_TRY(launch_embed_packed(ids_dev, cu, nullptr, B, T, wte, V, wpe, P, H, dtype, x_packed,
+                              static_cast<hipStream_t>(stream)));
+  return ENERGON_OK;
+}
+
+int energon_embed_at(const int32_t* ids_dev, const int32_t* positions_dev, int64_t n, const void* wte, int32_t V,
+                     const void* wpe, int32_t P, int32_t H, int32_t dtype, void* x, void* stream) {
+  if (!ids_dev || !positions_dev || !wte || !wpe || !x) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (n < 0 || n >= ((int64_t)1 << 31) || V <= 0 || P <= 0 || H <= 0 || H % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (!aligned16(wte) || !aligned16(wpe) || !aligned16(x) || (reinterpret_cast<uintptr_t>(ids_dev) & 3u) ||
+      (reinterpret_cast<uintptr_t>(positions_dev) & 3u))
+    return ENERGON_ERR_ALIGN;
+  HIP_TRY(launch_embed_packed(ids_dev, nullptr, positions_dev, 1, n, wte, V, wpe, P, H, dtype, x,
+                              static_cast<hipStream_t>(stream)));
   return ENERGON_OK;
 }
 

@@ -224,3 +224,18 @@ def test_decode_and_model_end_entry_points_reject_bad_arguments():
     assert r(FAKE, None, 2, 64, E.BF16, FAKE, None) == -1
     assert r(FAKE, FAKE, 2, 60, E.BF16, FAKE, None) == -2
     assert r(FAKE, FAKE, 0, 64, E.BF16, FAKE, None) == 0
+
+
+def test_cache_fill_and_embed_at_reject_bad_arguments():
+    l = E.lib()
+    f = l.energon_cache_fill
+    assert f(FAKE, FAKE, 5, 2, 128, 8, E.BF16, None, FAKE, None) == -1
+    assert f(FAKE, FAKE, 5, 2, 100, 8, E.BF16, FAKE, FAKE, None) == -2
+    assert f(FAKE, FAKE, 5, 2, 128, 8, E.F32, FAKE, FAKE, None) == -6
+    assert f(FAKE, FAKE + 2, 5, 2, 128, 8, E.BF16, FAKE, FAKE, None) == -5
+    assert f(None, FAKE, 0, 2, 128, 8, E.BF16, FAKE, FAKE, None) == 0          # T = 0: nothing to do
+    e = l.energon_embed_at
+    assert e(FAKE, None, 4, FAKE, 100, FAKE, 16, 64, E.BF16, FAKE, None) == -1
+    assert e(FAKE, FAKE, 4, FAKE, 100, FAKE, 16, 60, E.BF16, FAKE, None) == -2
+    assert e(FAKE, FAKE, 4, FAKE, 100, FAKE, 16, 64, E.F32, FAKE, None) == -6
+    assert e(FAKE, FAKE, 0, FAKE, 100, FAKE, 16, 64, E.BF16, FAKE, None) == 0

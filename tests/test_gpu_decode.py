@@ -298,3 +298,93 @@ def test_decode_layer_with_split_contraction(dtype):
     ref, _, _ = orc.decode_layer(x, [(kc[b, :lens[b]], vc[b, :lens[b]]) for b in range(B)], p, w.n_heads, w.head_dim, w.ln_eps)
     assert_close(hz.to_host(outs[0]), ref, dtype, "step with a split FC2")
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+
+
+def test_cache_fill_bit_exact():
+    rng = np.random.default_rng(8)
+    lens = np.array([5, 0, 70, 1, 33], dtype=np.int32)
+    A, S_cap, dtype = 192, 64, wl.BF16           # one sequence is longer than the cache
+    T = int(lens.sum())
+    qkv = wl.round_to_dtype(rng.standard_normal((T, 3 * A)), dtype)
+    qd = hz.to_device(qkv, dtype)
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), device="cuda")
+    kc = torch.full((5, S_cap, A), 7.0, dtype=qd.dtype, device="cuda")
+    vc = torch.full((5, S_cap, A), 7.0, dtype=qd.dtype, device="cuda")
+    E.energon_cache_fill(qd, cu, kc, vc)
+    k_ref, v_ref = orc.cache_from_packed(qkv.astype(np.float64), lens, S_cap, A, fill=7.0)
+    assert np.array_equal(hz.to_host(kc), k_ref) and np.array_equal(hz.to_host(vc), v_ref)
+
+
+def test_prompt_then_two_generation_steps_end_to_end():
+    """A small GPT through the whole C ABI: packed embedding -> 2 layers on the packed prompt ->
+    caches from each layer's QKV stage -> last-token rows -> final LayerNorm -> logits; then two
+    generation steps with given next tokens (embedding at the cached position, 2 layers on the
+    caches, final LayerNorm, logits).  The oracle recomputes every set of logits from scratch with
+    the whole-sequence forward on the extended sequences."""
+    dtype = wl.BF16
+    V, P, H, nh, d, F, L = 512, 64, 256, 4, 64, 512, 2
+    A = nh * d
+    rng = np.random.default_rng(12)
+    w = wl.Workload("e2e", dtype, L, H, nh, d, F, 4, 24, "uniform", 1, 24)
+    lens = np.array([9, 1, 17, 5], dtype=np.int32)
+    B, steps = 4, 2
+    ids_all = [rng.integers(0, V, lens[b] + steps).astype(np.int32) for b in range(B)]   # prompt + forced tokens
+    wte = wl.round_to_dtype(rng.standard_normal((V, H)) * 0.5, dtype)
+    wpe = wl.round_to_dtype(rng.standard_normal((P, H)) * 0.1, dtype)
+    w_lm = wl.round_to_dtype(rng.standard_normal((V, H)) / np.sqrt(H), dtype)
+    lnf_g = wl.round_to_dtype(1 + 0.2 * rng.standard_normal(H), dtype)
+    lnf_b = wl.round_to_dtype(0.1 * rng.standard_normal(H), dtype)
+    layers = [wl.sample_layer(w, l) for l in range(L)]
+
+    def oracle_logits(cur_lens):
+        ids = np.concatenate([ids_all[b][:cur_lens[b]] for b in range(B)])
+        xp = orc.embed_packed(ids, cur_lens, wte.astype(np.float64), wpe.astype(np.float64))
+        y = orc.stack_forward(orc.unpack(xp, cur_lens, int(cur_lens.max())), cur_lens, layers, nh, d, w.ln_eps)
+        last = orc.last_token_rows(orc.pack(y, cur_lens), cur_lens)
+        return orc.linear(orc.layer_norm(last, lnf_g.astype(np.float64), lnf_b.astype(np.float64), w.ln_eps),
+                          w_lm.astype(np.float64), None)
+
+    # ---- GPU: prompt
+    cfg = hz.layer_config(H, nh, d, F, dtype, w.ln_eps)
+    dev = [hz.DeviceLayer(p, dtype) for p in layers]
+    wted, wped, wlmd, gd, bd = (hz.to_device(a, dtype) for a in (wte, wpe, w_lm, lnf_g, lnf_b))
+    T = int(lens.sum())
+    S_cap = 32
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), device="cuda")
+    ids_prompt = torch.tensor(np.concatenate([ids_all[b][:lens[b]] for b in range(B)]), device="cuda")
+    bufs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    E.energon_embed_packed(ids_prompt, cu, wted, wped, bufs[0])
+    ws = torch.empty(E.energon_workspace_bytes(cfg, T), dtype=torch.uint8, device="cuda")
+    qkv_off = E.energon_workspace_layout(cfg, T)[E.WS_QKV]
+    kc = [torch.zeros((B, S_cap, A), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    vc = [torch.zeros((B, S_cap, A), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    for i, layer in enumerate(dev):
+        E.energon_layer_forward(cfg, layer.struct, bufs[i & 1], bufs[(i + 1) & 1], T, cu, lens, int(lens.max()), ws)
+        qkv = ws[qkv_off: qkv_off + T * 3 * A * 2].view(torch.bfloat16).view(T, 3 * A)
+        E.energon_cache_fill(qkv, cu, kc[i], vc[i])
+    hidden = bufs[L & 1]
+    last = torch.empty((B, H), dtype=torch.bfloat16, device="cuda")
+    E.energon_last_token_rows(hidden, cu, last)
+
+    def logits_of(rows):
+        normed = torch.empty_like(rows)
+        E.energon_layernorm(rows, gd, bd, normed, w.ln_eps)
+        out = torch.empty((B, V), dtype=torch.bfloat16, device="cuda")
+        E.energon_linear(normed, wlmd, None, None, out, E.EPI_BIAS)
+        return hz.to_host(out)
+
+    assert_close(logits_of(last), oracle_logits(lens), dtype, "logits after the prompt")
+
+    # ---- GPU: generation steps with the given next tokens
+    cache_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    dws = torch.empty(E.energon_decode_workspace_bytes(cfg, B), dtype=torch.uint8, device="cuda")
+    xb = [torch.empty((B, H), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    cur = lens.copy()
+    for s in range(steps):
+        nxt = torch.tensor([ids_all[b][cur[b]] for b in range(B)], dtype=torch.int32, device="cuda")
+        E.energon_embed_at(nxt, cache_lens, wted, wped, xb[0])
+        for i, layer in enumerate(dev):
+            E.energon_decode_layer_forward(cfg, layer.struct, xb[i & 1], xb[(i + 1) & 1], cache_lens, cur, kc[i], vc[i], dws)
+        cache_lens += 1
+        cur = cur + 1
+        assert_close(logits_of(xb[L & 1]), oracle_logits(cur), dtype, f"logits after generation step {s + 1}")

@@ -77,3 +77,20 @@ def test_embed_packed_and_last_rows_closed_forms():
             assert x[t, j] == 3 * ids[t] + j + 100 * want_pos[t]
     last = O.last_token_rows(x, lens)
     assert np.array_equal(last[0], x[2]) and np.array_equal(last[2], x[4]) and np.all(last[1] == 0)
+
+
+def test_cache_from_packed_closed_form():
+    lens = np.array([2, 0, 3])
+    A, S_cap = 2, 4
+    T = int(lens.sum())
+    # packed row t holds (t, t) | (10 + t, 10 + t) | (20 + t, 20 + t)
+    qkv = np.stack([np.repeat([t, 10 + t, 20 + t], A) for t in range(T)]).astype(np.float64)
+    k, v = O.cache_from_packed(qkv, lens, S_cap, A, fill=-1.0)
+    want_rows = {(0, 0): 0, (0, 1): 1, (2, 0): 2, (2, 1): 3, (2, 2): 4}
+    for b in range(3):
+        for i in range(S_cap):
+            if (b, i) in want_rows:
+                t = want_rows[(b, i)]
+                assert np.all(k[b, i] == 10 + t) and np.all(v[b, i] == 20 + t)
+            else:
+                assert np.all(k[b, i] == -1.0) and np.all(v[b, i] == -1.0)
