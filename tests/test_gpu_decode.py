@@ -388,3 +388,63 @@ def test_prompt_then_two_generation_steps_end_to_end():
         cache_lens += 1
         cur = cur + 1
         assert_close(logits_of(xb[L & 1]), oracle_logits(cur), dtype, f"logits after generation step {s + 1}")
+
+
+def test_generation_steps_replayed_from_a_hip_graph():
+    """The step reads its lengths from device memory and copies nothing from the host, so a whole
+    step (2 layers + advancing the lengths) can be captured once and replayed.  Every replay is
+    checked against the same step done eagerly, with eager work between the replays."""
+    dtype = wl.BF16
+    w = wl.Workload("dec_graph", dtype, 2, 256, 4, 64, 512, 3, 16, "uniform", 0, 16)
+    layers = [wl.sample_layer(w, 0), wl.sample_layer(w, 1)]
+    dev = [hz.DeviceLayer(p, dtype) for p in layers]
+    B, S_cap, A = 3, 16, w.attn_width
+    rng = np.random.default_rng(5)
+    xs = [hz.to_device(wl.round_to_dtype(rng.standard_normal((B, w.hidden)), dtype), dtype) for _ in range(4)]
+    start = np.array([0, 5, 2], dtype=np.int32)
+
+    def fresh():
+        st = DecodeState(w, B, S_cap, dev)
+        st.lens.copy_(torch.tensor(start, device="cuda"))
+        g = torch.Generator(device="cuda").manual_seed(1)
+        for i in range(2):
+            st.k[i].copy_(torch.randn((B, S_cap, A), device="cuda", generator=g).to(torch.bfloat16))
+            st.v[i].copy_(torch.randn((B, S_cap, A), device="cuda", generator=g).to(torch.bfloat16))
+        return st
+
+    def body(st, x_in):
+        src = x_in
+        for i, layer in enumerate(st.layers):
+            E.energon_decode_layer_forward(st.cfg, layer.struct, src, st.buf[i & 1], st.lens, None, st.k[i], st.v[i], st.ws)
+            src = st.buf[i & 1]
+        st.lens += 1
+        return src
+
+    eager = fresh()
+    want = [body(eager, x).clone() for x in xs]
+
+    st = fresh()
+    x_static = torch.empty_like(xs[0])
+    x_static.copy_(xs[0])
+    side = torch.cuda.Stream()                  # warm-up off the default stream, as capture requires
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        body(st, x_static)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    st = fresh()                                # undo the warm-up's append and length change
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out_static = body(st, x_static)
+    st2_lens_after_capture = st.lens.clone()    # capture itself must not have run the step
+    assert torch.equal(st2_lens_after_capture.cpu(), torch.tensor(start))
+    for i, x in enumerate(xs):
+        x_static.copy_(x)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_static.view(torch.int16), want[i].view(torch.int16)), f"replay {i} differs from eager"
+        _ = (xs[0].float() @ xs[0].float().T).sum().item()   # unrelated eager work and a sync between replays
+    assert torch.equal(st.lens.cpu(), torch.tensor(start + len(xs)))
+    for i in range(2):
+        assert torch.equal(st.k[i].view(torch.int16), eager.k[i].view(torch.int16))
+        assert torch.equal(st.v[i].view(torch.int16), eager.v[i].view(torch.int16))
