@@ -69,18 +69,24 @@ __device__ __forceinline__ bool tile_origin(int32_t tiles_m, int32_t tiles_n, in
 
 // Epilogue of one wavefront: TM x TN accumulator tiles of 32x32 whose top-left element is
 // (mw, nw).  In each tile the lane holds column (lane & 31), rows 8*(e/4) + 4*(lane/32) + e%4.
-template <typename E, int TM, int TN>
+// FOLD: the LayerNorm-folded epilogues are compiled into their own instantiation, so that the plain
+// one stays as small as it was (small problems are sensitive to it: 5 us per launch measured).
+template <typename E, int TM, int TN, bool FOLD>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const E* __restrict__ bias,
                                            const E* res, E* y, int64_t M, int32_t N, int epi, int64_t mw,
                                            int32_t nw, int lane, const LnFold& lf) {
   const int lrow = lane & 31, lhalf = lane >> 5;
-  const bool fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
+  constexpr bool fold = FOLD;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int32_t n = nw + j * 32 + lrow;
     const bool n_ok = n < N;
-    const float bv = !n_ok ? 0.f : fold ? lf.bias[n] : bias != nullptr ? static_cast<float>(bias[n]) : 0.f;
-    const float cv = (fold && n_ok) ? lf.colsum[n] : 0.f;
+    float bv = 0.f, cv = 0.f;
+    if constexpr (fold) {
+      if (n_ok) { bv = lf.bias[n]; cv = lf.colsum[n]; }
+    } else {
+      if (bias != nullptr && n_ok) bv = static_cast<float>(bias[n]);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -88,7 +94,7 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const E*
         const int64_t m = mw + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
         if (n_ok && m < M) {
           float v = acc[i][j][e];
-          if (fold) {
+          if constexpr (fold) {
             const float2 st = *reinterpret_cast<const float2*>(lf.stats + 2 * m);
             v = st.y * (v - st.x * cv);
           }
@@ -218,7 +224,7 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
 }
 
 // ---- compiler-scheduled tile kernel ---------------------------------------------------------
-template <typename E, int BM, int BN, int WM, int WN>
+template <typename E, int BM, int BN, int WM, int WN, bool FOLD>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __restrict__ x,
                                                                      const E* __restrict__ w,
                                                                      const E* __restrict__ bias,
@@ -331,7 +337,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
     __syncthreads();
   }
 
-  store_tile<E, TM, TN>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane, lf);
+  store_tile<E, TM, TN, FOLD>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane, lf);
 }
 
 // ---- hand-scheduled 256x256 kernel ----------------------------------------------------------
@@ -600,7 +606,7 @@ template <typename E>
 static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
                                    int32_t K, int epi, hipStream_t s, const LnFold* fold) {
   if (M <= 0) return hipSuccess;
-  static bool attr_big = false, attr_small = false;  // per element type
+  static bool attr_big = false, attr_small = false, attr_small_fold = false;  // per element type
   const LnFold lf = fold != nullptr ? *fold : LnFold{};
   const bool wants_fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
   if (wants_fold && (lf.stats == nullptr || lf.colsum == nullptr || lf.bias == nullptr)) return hipErrorInvalidValue;
@@ -613,7 +619,18 @@ static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const 
     return launch_tiles<E>(gemm_mfma_sched_kernel<E, 256, 256, 2, 2>, attr_big, 256, 256, 256,
                            slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, lf, s);
   }
-  return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2>, attr_small, 128, 128, 256,
+  // Few 128x128 tiles leave most of the 256 CUs idle: 64x64 tiles give four times as many workgroups
+  // (measured: 593 x 1024 x 4096 44 -> 33 us, 128 x 15360 x 5120 60 -> 44 us).
+  const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
+  if (tiles128 < 128 && !wants_fold) {
+    static bool attr_64 = false;
+    return launch_tiles<E>(gemm_mfma_tile_kernel<E, 64, 64, 2, 2, false>, attr_64, 64, 64, 256,
+                           2 * (size_t)(64 + 64) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
+  }
+  if (wants_fold)
+    return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2, true>, attr_small_fold, 128, 128, 256,
+                           2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
+  return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2, false>, attr_small, 128, 128, 256,
                          2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
 }
 
