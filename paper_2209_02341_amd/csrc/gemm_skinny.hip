@@ -7,10 +7,10 @@
 //    add their partial sums through LDS at the end, in a fixed order.  With K cut over KS
 //    workgroups (only where the caller provides room for KS fp32 partial results) a second small
 //    kernel adds the parts in a fixed order and applies the epilogue.  Deterministic, no atomics;
-//  * a slab of W (32 rows x 128 bytes) and the same slab of x (16 MT rows x 128 bytes) go from
-//    global memory straight to LDS (global_load_lds_dwordx4, whole 128-byte lines) into a ring
-//    that is private to the wavefront, 3-4 slabs deep: no barrier and no staging register in the
-//    streaming loop.  x is read again by every workgroup, from the L2; fetched as whole lines it
+//  * a slab of W (32 or 64 rows x 128 bytes) and the same slab of x (16 MT rows x 128 bytes) go
+//    from global memory straight to LDS (global_load_lds_dwordx4, whole 128-byte lines) into a
+//    ring that is private to the wavefront, 2 or 4 slabs deep (the depth made no measurable
+//    difference): no barrier and no staging register in the streaming loop.  x is read again by every workgroup, from the L2; fetched as whole lines it
 //    costs the W stream 20 % (measured in a probe: 24.7 -> 29.6 us for a 157 MB matrix), as 64-byte
 //    operand gathers into registers 60 %.  The XOR swizzle of the 256x256 kernel keeps the operand
 //    reads free of bank conflicts;
