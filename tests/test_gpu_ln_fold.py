@@ -210,3 +210,27 @@ def test_folded_full_size_13b_shape_sampled_sequences():
     yz = y_folded.float().abs().sum(dim=2).cpu().numpy()
     for bb in range(w.batch):
         assert np.all(yz[bb, lens[bb]:] == 0) and np.all(yz[bb, :lens[bb]] > 0)
+
+
+@pytest.mark.parametrize("mean", [8.0, 60.0])
+def test_linear_ln_folded_rows_far_from_zero(mean):
+    """The folded form subtracts mu * c from the contraction of the un-normalised rows: with a row
+    mean many standard deviations from zero that difference cancels most of both terms.  fp32
+    accumulation keeps it within the storage type's tolerance (bf16 rows around 60 carry only two
+    or three bits below the unit, so the rows themselves are coarse; the oracle sees the same rows)."""
+    M, N, K, dtype = 300, 264, 1024, wl.BF16
+    rng = np.random.default_rng(int(mean))
+    x = wl.round_to_dtype(rng.normal(mean, 1.0, (M, K)), dtype)
+    w = wl.round_to_dtype(rng.standard_normal((N, K)) / np.sqrt(K), dtype)
+    b = wl.round_to_dtype(rng.standard_normal(N) * 0.5, dtype)
+    g = wl.round_to_dtype(1.0 + 0.2 * rng.standard_normal(K), dtype)
+    beta = wl.round_to_dtype(0.3 * rng.standard_normal(K), dtype)
+    wf, c, bf = fold_on_gpu(w, b, g, beta, dtype)
+    xd = hz.to_device(x, dtype)
+    st = f32((M, 2))
+    E.energon_row_stats(xd, EPS, st)
+    yd = torch.empty((M, N), dtype=xd.dtype, device="cuda")
+    E.energon_linear_ln_folded(xd, wf, c, bf, st, yd, False)
+    ref = orc.linear(orc.layer_norm(x.astype(np.float64), g.astype(np.float64), beta.astype(np.float64), EPS),
+                     w.astype(np.float64), b.astype(np.float64))
+    assert_close(hz.to_host(yd), ref, dtype, f"folded linear, row mean {mean}")
