@@ -126,10 +126,15 @@ hipError_t launch_gemm_f32(const float* x, const float* w, const float* bias, co
                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s);
 // true if the launch for this shape can fill LnFold::partial (else the caller takes the statistics itself)
 bool gemm_emits_row_partials(int64_t M, int32_t N, int32_t K, bool res_aliases_y);
+// split_scratch (optional, gemm_scratch_bytes(M, N, K) bytes): lets problems with few rows cut K over
+// several workgroups (partial sums in fp32, added in a fixed order by a second kernel).
+size_t gemm_split_scratch_bytes(int64_t M, int32_t N, int32_t K);
 hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
-                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
+                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr,
+                            float* split_scratch = nullptr);
 hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y,
-                           int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr);
+                           int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr,
+                           float* split_scratch = nullptr);
 // gemm_skinny.hip: M <= 64 rows (a generation step), bound by streaming W once.  With `partial`
 // (gemm_skinny_partial_bytes bytes of scratch) K may be cut over several workgroups.
 bool gemm_skinny_takes(int64_t M, int32_t N, int32_t K, int epi);
@@ -137,6 +142,10 @@ size_t gemm_skinny_partial_bytes(int64_t M, int32_t N, int32_t K);
 template <typename E>
 hipError_t launch_gemm_skinny(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
                               int32_t K, int epi, hipStream_t s, float* partial = nullptr);
+// y = epilogue(sum over kz < KS of partial[kz][M][N] + b), the parts added in the order of kz
+template <typename E>
+hipError_t launch_partial_reduce(const float* partial, int32_t KS, const E* bias, const E* res, E* y, int64_t M,
+                                 int32_t N, int epi, hipStream_t s);
 // decode_attention.hip, model_ends.hip (dtype 1 or 2 only)
 hipError_t launch_decode_attention(const void* qkv, void* k_cache, void* v_cache, const int32_t* lens, int32_t B,
                                    int32_t S_cap, int32_t nh, int32_t d, int dtype, void* out, hipStream_t s);

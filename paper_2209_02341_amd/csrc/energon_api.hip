@@ -55,23 +55,14 @@ WsLayout ws_layout(const EnergonLayerConfig* c, int64_t T) {
 
 int linear_impl(const void* x, const void* w, const void* bias, const void* res, void* y, int64_t M, int32_t N,
                 int32_t K, int32_t epi, int32_t dt, hipStream_t s, const LnFold* fold = nullptr,
-                float* skinny_partial = nullptr) {
-  if (skinny_partial != nullptr && is16(dt) && gemm_skinny_takes(M, N, K, epi)) {
-    // few rows and scratch for partial sums: K may be cut over several workgroups
-    if (dt == ENERGON_BF16)
-      HIP_TRY(launch_gemm_skinny<bf16_t>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, (const bf16_t*)res,
-                                         (bf16_t*)y, M, N, K, epi, s, skinny_partial));
-    else
-      HIP_TRY(launch_gemm_skinny<f16_t>((const f16_t*)x, (const f16_t*)w, (const f16_t*)bias, (const f16_t*)res,
-                                        (f16_t*)y, M, N, K, epi, s, skinny_partial));
-    return ENERGON_OK;
-  }
+                float* split_scratch = nullptr) {
+  // split_scratch: room for fp32 partial sums, so that problems with few rows may cut K over workgroups
   if (dt == ENERGON_BF16)
     HIP_TRY(launch_gemm_bf16((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, (const bf16_t*)res, (bf16_t*)y,
-                             M, N, K, epi, s, fold));
+                             M, N, K, epi, s, fold, split_scratch));
   else if (dt == ENERGON_F16)
     HIP_TRY(launch_gemm_f16((const f16_t*)x, (const f16_t*)w, (const f16_t*)bias, (const f16_t*)res, (f16_t*)y, M, N,
-                            K, epi, s, fold));
+                            K, epi, s, fold, split_scratch));
   else if (fold != nullptr)
     return ENERGON_ERR_UNSUPPORTED;
   else
@@ -547,12 +538,13 @@ int energon_decode_attention(const void* qkv, void* k_cache, void* v_cache, cons
 
 // scratch for the partial sums of the few-row contractions of a step (the largest of the four)
 static size_t decode_partial_bytes(const EnergonLayerConfig* c, int32_t B) {
-  if (!is16(c->dtype) || B < 1 || B > 64) return 0;
+  if (!is16(c->dtype) || B < 1) return 0;
   const int32_t H = c->hidden, A = c->n_heads * c->head_dim, F = c->ffn;
   size_t m = 0;
   const int32_t shapes[4][2] = {{3 * A, H}, {H, A}, {F, H}, {H, F}};
   for (const auto& nk : shapes) {
-    const size_t b = gemm_skinny_takes(B, nk[0], nk[1], EPI_BIAS) ? gemm_skinny_partial_bytes(B, nk[0], nk[1]) : 0;
+    const size_t b = gemm_skinny_takes(B, nk[0], nk[1], EPI_BIAS) ? gemm_skinny_partial_bytes(B, nk[0], nk[1])
+                                                                  : gemm_split_scratch_bytes(B, nk[0], nk[1]);
     m = b > m ? b : m;
   }
   return round256(m);

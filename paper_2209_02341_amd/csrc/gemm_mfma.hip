@@ -108,6 +108,25 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], const E*
   }
 }
 
+// Split-K mode of the tile kernel: the raw fp32 sums of this workgroup's part of K, to
+// part[m][n] of its own [M, N] slice; a second kernel adds the slices in order and applies the epilogue.
+template <int TM, int TN>
+__device__ __forceinline__ void store_partial(const f32x16 (&acc)[TM][TN], float* __restrict__ part, int64_t M,
+                                              int32_t N, int64_t mw, int32_t nw, int lane) {
+  const int lrow = lane & 31, lhalf = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int32_t n = nw + j * 32 + lrow;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int64_t m = mw + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+        if (n < N && m < M) part[(size_t)m * N + n] = acc[i][j][e];
+      }
+  }
+}
+
 // Epilogue of one wavefront's 128x128 tile (8 x 8 accumulator tiles of 16x16; in each the lane
 // holds column lane % 16, rows 4 * (lane / 16) + e) through LDS, for tiles that lie wholly
 // inside the matrix.  The accumulators go to LDS as fp32, 64 rows at a time, rows padded to 132
@@ -224,7 +243,9 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
 }
 
 // ---- compiler-scheduled tile kernel ---------------------------------------------------------
-template <typename E, int BM, int BN, int WM, int WN, bool FOLD>
+// MODE 0: plain epilogues; 1: the LayerNorm-folded epilogues; 2: split K, gridDim.y parts, fp32 sums
+// of part blockIdx.y to lf.partial + blockIdx.y * M * N (lf.partial is the caller's scratch here).
+template <typename E, int BM, int BN, int WM, int WN, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __restrict__ x,
                                                                      const E* __restrict__ w,
                                                                      const E* __restrict__ bias,
@@ -249,8 +270,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
   // One direct-to-LDS load fills 1 KiB = 8 rows x 8 chunks; lane l lands at row l/8, slot l%8 of
   // the group, so it must fetch the chunk that the swizzle puts in that slot.
   // Byte offsets from the tile's first row (uniform base pointer + 32-bit lane offset).
-  const char* xbase = reinterpret_cast<const char*>(x + (size_t)m0 * K);
-  const char* wbase = reinterpret_cast<const char*>(w + (size_t)n0 * K);
+  const int KT = MODE == 2 ? K / BK / (int)gridDim.y : K / BK;                   // slabs of this workgroup
+  const size_t k0 = MODE == 2 ? (size_t)blockIdx.y * KT * (BK * sizeof(E)) : 0;   // byte offset of its first slab
+  const char* xbase = reinterpret_cast<const char*>(x + (size_t)m0 * K) + k0;
+  const char* wbase = reinterpret_cast<const char*>(w + (size_t)n0 * K) + k0;
   uint32_t oa[GA], ob[GB];
 #pragma unroll
   for (int i = 0; i < GA; ++i) {
@@ -282,7 +305,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   constexpr int kStage = (BM + BN) * kChunks;  // in uint4
-  const int KT = K / BK;
 
   auto issue = [&](int kt, int stage) {
     uint4* base = smem + stage * kStage;
@@ -337,7 +359,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
     __syncthreads();
   }
 
-  store_tile<E, TM, TN, FOLD>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane, lf);
+  if constexpr (MODE == 2)
+    store_partial<TM, TN>(acc, lf.partial + (size_t)blockIdx.y * M * N, M, N, m0 + wm0, n0 + wn0, lane);
+  else
+    store_tile<E, TM, TN, MODE == 1>(acc, bias, res, y, M, N, epi, m0 + wm0, n0 + wn0, lane, lf);
 }
 
 // ---- hand-scheduled 256x256 kernel ----------------------------------------------------------
@@ -572,7 +597,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
 template <typename E, typename Kern>
 static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int threads, size_t lds, const E* x,
                                const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
-                               int32_t K, int epi, const LnFold& lf, hipStream_t s) {
+                               int32_t K, int epi, const LnFold& lf, hipStream_t s, int32_t ks = 1) {
   if (!attr_set) {  // idempotent; a race between host threads only repeats the call
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -582,7 +607,8 @@ static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int th
   const int32_t tiles_m = (int32_t)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
   const int64_t total = (int64_t)tiles_m * tiles_n;
   const int64_t grid = (total + kXcds - 1) / kXcds * kXcds;
-  kern<<<dim3((unsigned)grid), dim3(threads), lds, s>>>(x, w, bias, res, y, M, N, K, epi, tiles_m, tiles_n, lf);
+  kern<<<dim3((unsigned)grid, (unsigned)ks), dim3(threads), lds, s>>>(x, w, bias, res, y, M, N, K, epi, tiles_m, tiles_n,
+                                                                       lf);
   return hipGetLastError();
 }
 
@@ -602,9 +628,28 @@ bool gemm_emits_row_partials(int64_t M, int32_t N, int32_t K, bool res_aliases_y
   return takes_sched_kernel(M, N, K, res_aliases_y) && N % 256 == 0;
 }
 
+// Tile size and number of K parts for the split path: enough workgroups (>= 512 where K allows), every
+// part at least 16 slabs long.
+void gemm_split_plan(int64_t M, int32_t N, int32_t K, int32_t* tile, int32_t* ks) {
+  const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
+  const int32_t t = tiles128 < 128 ? 64 : 128;
+  const int64_t tiles = ((M + t - 1) / t) * ((N + t - 1) / t);
+  const int32_t KT = K / BK;
+  int32_t k = 1;
+  while (k < 16 && tiles * k < 512 && KT % (2 * k) == 0 && KT / (2 * k) >= 16) k *= 2;
+  *tile = t;
+  *ks = k;
+}
+
+size_t gemm_split_scratch_bytes(int64_t M, int32_t N, int32_t K) {
+  int32_t tile, ks;
+  gemm_split_plan(M, N, K, &tile, &ks);
+  return ks > 1 ? (size_t)ks * (size_t)M * N * sizeof(float) : 0;
+}
+
 template <typename E>
 static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
-                                   int32_t K, int epi, hipStream_t s, const LnFold* fold) {
+                                   int32_t K, int epi, hipStream_t s, const LnFold* fold, float* split_scratch) {
   if (M <= 0) return hipSuccess;
   static bool attr_big = false, attr_small = false, attr_small_fold = false;  // per element type
   const LnFold lf = fold != nullptr ? *fold : LnFold{};
@@ -612,36 +657,56 @@ static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const 
   if (wants_fold && (lf.stats == nullptr || lf.colsum == nullptr || lf.bias == nullptr)) return hipErrorInvalidValue;
   if (lf.partial != nullptr && (epi != EPI_BIAS_RESIDUAL || !gemm_emits_row_partials(M, N, K, res == y)))
     return hipErrorInvalidValue;
-  if (lf.partial == nullptr && gemm_skinny_takes(M, N, K, epi)) return launch_gemm_skinny<E>(x, w, bias, res, y, M, N, K, epi, s);
+  if (lf.partial == nullptr && gemm_skinny_takes(M, N, K, epi))
+    return launch_gemm_skinny<E>(x, w, bias, res, y, M, N, K, epi, s, split_scratch);
   if (takes_sched_kernel(M, N, K, res == y)) {
     constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
     constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
     return launch_tiles<E>(gemm_mfma_sched_kernel<E, 256, 256, 2, 2>, attr_big, 256, 256, 256,
                            slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, lf, s);
   }
+  // A batch of a generation step too large for the few-row kernel, with scratch from the caller: K cut
+  // over workgroups until there are enough of them, the parts added by a second kernel.
+  if (split_scratch != nullptr && !wants_fold && lf.partial == nullptr) {
+    int32_t tile, ks;
+    gemm_split_plan(M, N, K, &tile, &ks);
+    if (ks > 1) {
+      LnFold sp;
+      sp.partial = split_scratch;
+      static bool attr_s64 = false, attr_s128 = false;
+      hipError_t e = tile == 64
+          ? launch_tiles<E>(gemm_mfma_tile_kernel<E, 64, 64, 2, 2, 2>, attr_s64, 64, 64, 256,
+                            2 * (size_t)(64 + 64) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, sp, s, ks)
+          : launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2, 2>, attr_s128, 128, 128, 256,
+                            2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, sp, s, ks);
+      if (e != hipSuccess) return e;
+      return launch_partial_reduce<E>(split_scratch, ks, bias, res, y, M, N, epi, s);
+    }
+  }
   // Few 128x128 tiles leave most of the 256 CUs idle: 64x64 tiles give four times as many workgroups
   // (measured: 593 x 1024 x 4096 44 -> 33 us, 128 x 15360 x 5120 60 -> 44 us).
   const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
   if (tiles128 < 128 && !wants_fold) {
     static bool attr_64 = false;
-    return launch_tiles<E>(gemm_mfma_tile_kernel<E, 64, 64, 2, 2, false>, attr_64, 64, 64, 256,
+    return launch_tiles<E>(gemm_mfma_tile_kernel<E, 64, 64, 2, 2, 0>, attr_64, 64, 64, 256,
                            2 * (size_t)(64 + 64) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
   }
   if (wants_fold)
-    return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2, true>, attr_small_fold, 128, 128, 256,
+    return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2, 1>, attr_small_fold, 128, 128, 256,
                            2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
-  return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2, false>, attr_small, 128, 128, 256,
+  return launch_tiles<E>(gemm_mfma_tile_kernel<E, 128, 128, 2, 2, 0>, attr_small, 128, 128, 256,
                          2 * (size_t)(128 + 128) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
-                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold) {
-  return launch_gemm_mfma<bf16_t>(x, w, bias, res, y, M, N, K, epi, s, fold);
+                            int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold,
+                            float* split_scratch) {
+  return launch_gemm_mfma<bf16_t>(x, w, bias, res, y, M, N, K, epi, s, fold, split_scratch);
 }
 
 hipError_t launch_gemm_f16(const f16_t* x, const f16_t* w, const f16_t* bias, const f16_t* res, f16_t* y, int64_t M,
-                           int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold) {
-  return launch_gemm_mfma<f16_t>(x, w, bias, res, y, M, N, K, epi, s, fold);
+                           int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold, float* split_scratch) {
+  return launch_gemm_mfma<f16_t>(x, w, bias, res, y, M, N, K, epi, s, fold, split_scratch);
 }
 
 }  // namespace energon

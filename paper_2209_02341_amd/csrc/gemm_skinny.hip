@@ -235,9 +235,7 @@ hipError_t launch_cfg(const E* x, const E* w, const E* bias, const E* res, E* y,
                                                                                       K, epi);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || partial == nullptr) return e;
-  const size_t total4 = (size_t)M * N / 4;
-  skinny_reduce_kernel<E><<<dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s>>>(partial, KS, bias, res, y, M, N, epi);
-  return hipGetLastError();
+  return launch_partial_reduce<E>(partial, KS, bias, res, y, M, N, epi, s);
 }
 
 template <typename E, int NT>
@@ -249,6 +247,20 @@ hipError_t launch_nt(const E* x, const E* w, const E* bias, const E* res, E* y, 
 }
 
 }  // namespace
+
+template <typename E>
+hipError_t launch_partial_reduce(const float* partial, int32_t KS, const E* bias, const E* res, E* y, int64_t M,
+                                 int32_t N, int epi, hipStream_t s) {
+  const size_t total4 = (size_t)M * N / 4;   // N % 4 == 0 for every caller (N % 8 == 0 is an ABI rule)
+  if (total4 == 0) return hipSuccess;
+  skinny_reduce_kernel<E><<<dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s>>>(partial, KS, bias, res, y,
+                                                                                       (int32_t)M, N, epi);
+  return hipGetLastError();
+}
+template hipError_t launch_partial_reduce<bf16_t>(const float*, int32_t, const bf16_t*, const bf16_t*, bf16_t*, int64_t,
+                                                  int32_t, int, hipStream_t);
+template hipError_t launch_partial_reduce<f16_t>(const float*, int32_t, const f16_t*, const f16_t*, f16_t*, int64_t,
+                                                 int32_t, int, hipStream_t);
 
 bool gemm_skinny_takes(int64_t M, int32_t N, int32_t K, int epi) {
   return M >= 1 && M <= 64 && N % 32 == 0 && K % 64 == 0 && epi >= EPI_BIAS && epi <= EPI_BIAS_RESIDUAL;

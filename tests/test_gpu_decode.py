@@ -448,3 +448,31 @@ def test_generation_steps_replayed_from_a_hip_graph():
     for i in range(2):
         assert torch.equal(st.k[i].view(torch.int16), eager.k[i].view(torch.int16))
         assert torch.equal(st.v[i].view(torch.int16), eager.v[i].view(torch.int16))
+
+
+def test_decode_layer_batch_above_the_few_row_kernel():
+    """96 sequences: more rows than the few-row kernel takes, few enough that the tiled kernel would
+    leave most CUs idle; with the step's scratch its K is cut over workgroups (QKV, out-proj, FC1
+    and FC2 all qualify at this shape).  Against the oracle, and run-to-run identical."""
+    dtype = wl.BF16
+    w = wl.Workload("dec_b96", dtype, 1, 2048, 16, 128, 8192, 96, 24, "uniform", 0, 24)
+    rng = np.random.default_rng(31)
+    B, S_cap, A = 96, 24, w.attn_width
+    lens = rng.integers(0, S_cap, B).astype(np.int32)
+    p = wl.sample_layer(w, 0)
+    kc = wl.round_to_dtype(rng.standard_normal((B, S_cap, A)), dtype)
+    vc = wl.round_to_dtype(rng.standard_normal((B, S_cap, A)), dtype)
+    x = wl.round_to_dtype(rng.standard_normal((B, w.hidden)), dtype)
+    cfg = hz.layer_config(w.hidden, w.n_heads, w.head_dim, w.ffn, dtype, w.ln_eps)
+    layer = hz.DeviceLayer(p, dtype)
+    ws = torch.empty(E.energon_decode_workspace_bytes(cfg, B), dtype=torch.uint8, device="cuda")
+    assert ws.numel() > E.energon_workspace_bytes(cfg, B), "no room for partial sums was planned"
+    outs = []
+    for _ in range(2):
+        xd, kd, vd = (hz.to_device(a, dtype) for a in (x, kc, vc))
+        y = torch.empty_like(xd)
+        E.energon_decode_layer_forward(cfg, layer.struct, xd, y, torch.tensor(lens, device="cuda"), lens, kd, vd, ws)
+        outs.append(y)
+    ref, _, _ = orc.decode_layer(x, [(kc[b, :lens[b]], vc[b, :lens[b]]) for b in range(B)], p, w.n_heads, w.head_dim, w.ln_eps)
+    assert_close(hz.to_host(outs[0]), ref, dtype, "step at batch 96")
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
