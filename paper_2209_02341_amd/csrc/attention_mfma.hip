@@ -258,12 +258,10 @@ static hipError_t launch_d(const E* q, const E* k, const E* v, E* out, const int
                            int32_t nh, hipStream_t s) {
   auto kern = attention_mfma_kernel<E, D, PADDED>;
   constexpr size_t lds = 2 * (size_t)(kBKV * D * 2 + D * kBKV * 2);
-  static bool attr_set = false;  // idempotent; a race between host threads only repeats the call
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static LdsAttrOnce once;
+  {
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, once);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   const int32_t n_qblocks = (max_len + kBQ - 1) / kBQ;
   const int32_t n_pairs = B * nh;

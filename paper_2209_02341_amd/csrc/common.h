@@ -93,6 +93,21 @@ __device__ inline float gelu_erf(float z) {
   return fmaf(-0.5f * a, e, fmaxf(z, 0.f));
 }
 
+// Kernels that use more dynamic LDS than the default limit must be told so once per device (the
+// attribute belongs to the kernel on a device).  One flag per device; a race between host threads
+// only repeats the call.
+struct LdsAttrOnce { bool done[32] = {}; };
+inline hipError_t ensure_dynamic_lds(const void* kern, size_t bytes, LdsAttrOnce& once) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 32;
+  if (tracked && once.done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && tracked) once.done[dev] = true;
+  return e;
+}
+
 enum Epilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_LNFOLD = 3, EPI_LNFOLD_GELU = 4 };
 
 // LayerNorm folded into a 16-bit linear (the fusion of Sec. 5.5's comparison system, in algebraic

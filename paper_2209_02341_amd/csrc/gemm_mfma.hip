@@ -595,14 +595,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
 }
 
 template <typename E, typename Kern>
-static hipError_t launch_tiles(Kern kern, bool& attr_set, int BM, int BN, int threads, size_t lds, const E* x,
+static hipError_t launch_tiles(Kern kern, LdsAttrOnce& attr_set, int BM, int BN, int threads, size_t lds, const E* x,
                                const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
                                int32_t K, int epi, const LnFold& lf, hipStream_t s, int32_t ks = 1) {
-  if (!attr_set) {  // idempotent; a race between host threads only repeats the call
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  {
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, attr_set);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   const int32_t tiles_m = (int32_t)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
   const int64_t total = (int64_t)tiles_m * tiles_n;
@@ -651,7 +649,7 @@ template <typename E>
 static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
                                    int32_t K, int epi, hipStream_t s, const LnFold* fold, float* split_scratch) {
   if (M <= 0) return hipSuccess;
-  static bool attr_big = false, attr_small = false, attr_small_fold = false;  // per element type
+  static LdsAttrOnce attr_big, attr_small, attr_small_fold;  // per element type
   const LnFold lf = fold != nullptr ? *fold : LnFold{};
   const bool wants_fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
   if (wants_fold && (lf.stats == nullptr || lf.colsum == nullptr || lf.bias == nullptr)) return hipErrorInvalidValue;
@@ -673,7 +671,7 @@ static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const 
     if (ks > 1) {
       LnFold sp;
       sp.partial = split_scratch;
-      static bool attr_s64 = false, attr_s128 = false;
+      static LdsAttrOnce attr_s64, attr_s128;
       hipError_t e = tile == 64
           ? launch_tiles<E>(gemm_mfma_tile_kernel<E, 64, 64, 2, 2, 2>, attr_s64, 64, 64, 256,
                             2 * (size_t)(64 + 64) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, sp, s, ks)
@@ -687,7 +685,7 @@ static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const 
   // (measured: 593 x 1024 x 4096 44 -> 33 us, 128 x 15360 x 5120 60 -> 44 us).
   const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
   if (tiles128 < 128 && !wants_fold) {
-    static bool attr_64 = false;
+    static LdsAttrOnce attr_64;
     return launch_tiles<E>(gemm_mfma_tile_kernel<E, 64, 64, 2, 2, 0>, attr_64, 64, 64, 256,
                            2 * (size_t)(64 + 64) * kChunks * sizeof(uint4), x, w, bias, res, y, M, N, K, epi, lf, s);
   }

@@ -224,12 +224,10 @@ hipError_t launch_cfg(const E* x, const E* w, const E* bias, const E* res, E* y,
                       int32_t N, int32_t K, int epi, hipStream_t s) {
   auto kern = gemm_skinny_kernel<E, MT, NT>;
   constexpr size_t lds = SkCfg<MT, NT>::kLds;
-  static bool attr_set = false;  // idempotent; a race between host threads only repeats the call
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static LdsAttrOnce once;
+  {
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, once);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   kern<<<dim3((unsigned)(N / (16 * NT)), (unsigned)KS), dim3(kSkWaves * 64), lds, s>>>(x, w, bias, res, y, partial, M, N,
                                                                                       K, epi);
