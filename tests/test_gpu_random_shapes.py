@@ -108,3 +108,64 @@ def test_decode_attention_random_lengths(lens, S_cap, nh, d, dtype):
         ref = orc.decode_attention(q64[b, :A], q64[b, A:2 * A], q64[b, 2 * A:], kc[b, :p].astype(np.float64),
                                    vc[b, :p].astype(np.float64), nh, d)
         assert_close(got[b][None, :], ref[None, :], dtype, f"decode attention seq {b} (cached {p})")
+
+
+def layer_cases():
+    rng = np.random.default_rng(4242)
+    cases = []
+    for i in range(6):
+        d = int(rng.choice([64, 128]))
+        nh = int(rng.integers(1, 5))
+        H = 64 * int(rng.integers(1, 9))
+        F = 64 * int(rng.integers(1, 17))
+        B = int(rng.integers(1, 7))
+        S = int(rng.integers(4, 150))
+        lens = [int(v) for v in rng.integers(0, S + 1, B)]
+        cases.append((H, nh, d, F, S, lens, wl.BF16 if i % 3 else wl.F16))
+    return cases
+
+
+@pytest.mark.parametrize("H,nh,d,F,S,lens,dtype", layer_cases())
+def test_layer_paths_random_config(H, nh, d, F, S, lens, dtype):
+    """One random layer configuration through the three prefill paths (plain, the paper's attention
+    path, LayerNorm folded) and, from the caches of that prefill, one generation step."""
+    B = len(lens)
+    lens = np.array(lens, dtype=np.int32)
+    w = wl.Workload("rand", dtype, 1, H, nh, d, F, B, S, "uniform", 0, S)
+    rng = np.random.default_rng(H + F + S)
+    x = wl.round_to_dtype(rng.standard_normal((B, S + 1, H)), dtype)     # one extra token per sequence for the step
+    # weight scale 0.05 keeps the attention logits at a standard deviation of 1-2: at 0.1 they reach 5-6
+    # and the 2^-9 rounding of q and k alone moves attention weights by more than the bf16 tolerance
+    p = wl.random_small_layer(rng, H, nh, d, F, dtype=dtype, std=0.05)
+    A = nh * d
+    st = {}
+    ref = orc.stack_forward(x[:, :S], lens, [p], nh, d, w.ln_eps, stages=st)
+    cfg = hz.layer_config(H, nh, d, F, dtype, w.ln_eps)
+    layer = hz.DeviceLayer(p, dtype)
+    T = int(lens.sum())
+    run = hz.PackedRun(cfg, B, S, T)
+    xd = hz.to_device(x[:, :S].copy(), dtype)
+    y = hz.to_host(run.forward(xd, lens, [layer]).clone())
+    assert_close(orc.pack(y, lens), orc.pack(ref, lens), dtype, "plain path")
+    # caches from this prefill's QKV stage, then one step with the extra token
+    S_cap = S + 1
+    kc = torch.zeros((B, S_cap, A), dtype=xd.dtype, device="cuda")
+    vc = torch.zeros_like(kc)
+    if T:
+        E.energon_cache_fill(run.stage(E.WS_QKV, 3 * A), run.cu, kc, vc)
+    y_fold = hz.to_host(run.forward_folded(xd, lens, [hz.FoldedDeviceLayer(layer)]).clone())
+    assert_close(orc.pack(y_fold, lens), orc.pack(ref, lens), dtype, "folded path")
+    if T:
+        padws = torch.empty(E.energon_drce_workspace_bytes(cfg, B, S), dtype=torch.uint8, device="cuda")
+        yp = torch.empty_like(run.x_packed)
+        E.energon_pack(xd, lens, run.x_packed, run.cu, run.idx)
+        E.energon_layer_forward_drce(cfg, layer.struct, run.x_packed, yp, T, run.cu, lens, S, run.workspace, padws)
+        assert_close(hz.to_host(yp[:T]), orc.pack(ref, lens), dtype, "paper's attention path")
+    x_new = np.stack([x[b, lens[b]] for b in range(B)])
+    ref_step = orc.layer_forward_padded(x, lens + 1, p, nh, d, w.ln_eps)
+    want = np.stack([ref_step[b, lens[b]] for b in range(B)])
+    xn = hz.to_device(x_new, dtype)
+    yn = torch.empty_like(xn)
+    dws = torch.empty(E.energon_decode_workspace_bytes(cfg, B), dtype=torch.uint8, device="cuda")
+    E.energon_decode_layer_forward(cfg, layer.struct, xn, yn, torch.tensor(lens, device="cuda"), lens, kc, vc, dws)
+    assert_close(hz.to_host(yn), want, dtype, "generation step after the prefill")
