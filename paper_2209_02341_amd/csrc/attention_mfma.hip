@@ -15,9 +15,9 @@
 // so the online-softmax state (running max, running sum) is one scalar per lane, and the
 // exponentiated scores are already laid out as the B operand of the second product: no
 // cross-lane movement of P.  The contraction index (key) may be enumerated in any order as long
-// as both operands agree, so V^T is read from LDS in the order the accumulator layout dictates:
-// slot 8 * (lane / 16) + i of a 32-key step is key 4 * (lane / 16) + i (i < 4) or 16 + 4 *
-// (lane / 16) + i - 4 of that step.
+// as both operands agree, so V^T is kept in LDS in the order the accumulator layout dictates:
+// position 8 g + i of a 32-key step holds key 4 g + i (i < 4) or 16 + 4 g + i - 4 of that step,
+// which makes a lane's 8 keys (g = lane / 16) one 16-byte read.
 // K tiles go from global memory straight to LDS (global_load_lds_dwordx4, the swizzle applied on
 // the global side); V is transposed on its way into LDS (key-contiguous rows), two keys per
 // 32-bit store, through registers.
@@ -34,7 +34,11 @@ typedef __attribute__((address_space(3))) void* attn_lptr_t;
 template <int D> __device__ __forceinline__ int kswz(int row) {
   return D == 128 ? (row & 15) : ((row & 7) ^ ((row >> 3) & 1));
 }
-__device__ __forceinline__ int vswz(int dd) { return (dd >> 1) & 7; }
+// V^T rows are 128 bytes (64 keys); a lane reads row dd % 16 of a 16-row block, chunk 4 s + lane / 16:
+// the access shape of the GEMM's 16-row operand tiles, and the same conflict-free swizzle.
+__device__ __forceinline__ int vswz(int dd) {
+  return ((dd >> 1) & 1) | (((dd >> 2) & 1) << 2) | (((dd >> 3) & 1) << 1);
+}
 
 // PADDED = false: Q, K, V are thirds of the packed [T, 3A] rows, the output is packed [T, A], and
 // only the len[b] real queries of a sequence are computed.  PADDED = true (the paper's own path,
@@ -119,7 +123,10 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int dd = (wave + kAttnWaves * j) * 8 + 2 * e + odd;
-      vdst[j][e] = (uint32_t)(dd * 32 + (((kp >> 2) ^ vswz(dd)) * 4) + (kp & 3));
+      // key pair kp = 16 s + 8 h + 2 g + i (keys 32 s + 16 h + 4 g + 2 i, + 1) goes to 16-byte chunk
+      // 4 s + g of the row, word 2 h + i of the chunk
+      const int chunk = 4 * (kp >> 4) + ((kp >> 1) & 3), word = 2 * ((kp >> 3) & 1) + (kp & 1);
+      vdst[j][e] = (uint32_t)(dd * 32 + ((chunk ^ vswz(dd)) * 4) + word);
     }
 
   // Tile t+1 is fetched while tile t is consumed: K straight into the other LDS buffer (free since
@@ -206,17 +213,15 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
 #pragma unroll
           for (int e = 0; e < 4; ++e) oacc[i][e] *= corr;
       }
-      // O^T += V^T P^T ; step s covers keys 32 s + {4 g4 .. 4 g4 + 3, 16 + 4 g4 .. 16 + 4 g4 + 3}
+      // O^T += V^T P^T ; step s, lane group g4: keys 32 s + {4 g4 .. 4 g4 + 3, 16 + 4 g4 .. 16 + 4 g4 + 3},
+      // adjacent in the V^T row by construction
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
 #pragma unroll
         for (int i = 0; i < DB; ++i) {
           const int dd = i * 16 + lq;
-          const char* rowp = vt + dd * 128 + 8 * (g4 & 1);
-          const uint2 lo = *reinterpret_cast<const uint2*>(rowp + (((4 * s + (g4 >> 1)) ^ vswz(dd)) * 16));
-          const uint2 hi = *reinterpret_cast<const uint2*>(rowp + (((4 * s + 2 + (g4 >> 1)) ^ vswz(dd)) * 16));
           union { uint4 u; vec8<E> v; } vf;
-          vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          vf.u = *reinterpret_cast<const uint4*>(vt + dd * 128 + (((4 * s + g4) ^ vswz(dd)) * 16));
           oacc[i] = Mfma<E>::m16x16x32(vf.v, pf[s], oacc[i]);
         }
       }
