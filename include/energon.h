@@ -335,6 +335,23 @@ int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLay
                                  void* k_cache, void* v_cache, int32_t S_cap, void* workspace_dev,
                                  size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels
+ * and results as energon_decode_layer_forward, minus the workspace: the intermediates live in a
+ * fixed array of ENERGON_STATIC_SCRATCH_BYTES of device memory inside the library (one copy per GPU
+ * that loads it, held until the process ends; its address is looked up once per device, on the
+ * first call made with that device current).  The call allocates and frees nothing.
+ * ENERGON_ERR_CAPACITY if energon_decode_workspace_bytes(cfg, B) exceeds the array (at the
+ * hidden-5120 layer of the benchmark: batches up to 160 rows).  All calls on one GPU share the array, which
+ * keeps the previous call's contents (nothing in it needs clearing: every stage overwrites what the
+ * next one reads): calls on the same GPU must be ordered on one stream or otherwise serialised;
+ * two that overlap race. */
+#define ENERGON_STATIC_SCRATCH_BYTES (64u << 20)
+int energon_decode_layer_forward_static(const EnergonLayerConfig* cfg, const EnergonLayerWeights* weights,
+                                        const void* x, void* y, int32_t B, const int32_t* cache_lens_dev,
+                                        const int32_t* cache_lens_host, void* k_cache, void* v_cache,
+                                        int32_t S_cap, void* stream);
+
 /* ---- The two ends of the model on the packed layout (bf16 / fp16) -----------------------------
  * The paper names the embedding layer (Sec. 2.2) without describing it; learned absolute
  * positions as in the GPT models it runs. */

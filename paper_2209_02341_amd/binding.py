@@ -92,6 +92,8 @@ def lib() -> C.CDLL:
         l.energon_decode_workspace_bytes.restype = sz
         l.energon_decode_workspace_bytes.argtypes = [pcfg, i32]
         l.energon_decode_layer_forward.argtypes = [pcfg, pw, vp, vp, i32, vp, vp, vp, vp, i32, vp, sz, vp]
+        l.energon_decode_layer_forward_static.argtypes = [pcfg, pw, vp, vp, i32, vp, vp, vp, vp, i32, vp]
+        l.energon_decode_layer_forward_static.restype = C.c_int
         l.energon_embed_packed.argtypes = [vp, vp, i64, i32, vp, i32, vp, i32, i32, i32, vp, vp]
         l.energon_embed_at.argtypes = [vp, vp, i64, vp, i32, vp, i32, i32, i32, vp, vp]
         l.energon_embed_at.restype = C.c_int
@@ -357,6 +359,20 @@ def energon_decode_layer_forward(cfg: LayerConfig, weights: LayerWeights, x, y, 
                                               _ptr(cache_lens_dev), _ptr(lens), _ptr(k_cache), _ptr(v_cache), S_cap,
                                               _ptr(workspace), int(workspace.numel() * workspace.element_size()),
                                               _stream(stream)), "energon_decode_layer_forward")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20   # ENERGON_STATIC_SCRATCH_BYTES
+
+
+def energon_decode_layer_forward_static(cfg: LayerConfig, weights: LayerWeights, x, y, cache_lens_dev,
+                                        cache_lens_host, k_cache, v_cache, stream=None) -> None:
+    """energon_decode_layer_forward without a workspace argument (the library's fixed scratch array)."""
+    B, S_cap = k_cache.shape[0], k_cache.shape[1]
+    lens = None if cache_lens_host is None else _lengths(cache_lens_host)
+    _check(lib().energon_decode_layer_forward_static(C.byref(cfg), C.byref(weights), _ptr(x), _ptr(y), B,
+                                                     _ptr(cache_lens_dev), _ptr(lens), _ptr(k_cache),
+                                                     _ptr(v_cache), S_cap, _stream(stream)),
+           "energon_decode_layer_forward_static")
 
 
 def energon_embed_packed(ids_dev, cu_seqlens, wte, wpe, x_packed, stream=None) -> None:

@@ -2,6 +2,7 @@
 // the kernel launches of each stage, all on the caller's stream.  No allocation, no state.
 #include "../../include/energon.h"
 #include "common.h"
+#include <mutex>
 
 using namespace energon;
 
@@ -246,6 +247,30 @@ int layer_timed(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, con
 }
 
 }  // namespace
+
+// Scratch for the entry point that may not allocate (energon_decode_layer_forward_static): the
+// layer's intermediates and the partial sums of its contractions live in this array instead of a
+// caller's workspace.  Every GPU that loads the library holds its own copy until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the device address is
+// looked up once per device, with that device current, and only that address is ever handed to a
+// kernel.  Nothing in it has to start at zero (every stage overwrites what the next one reads).
+static __device__ __align__(256) unsigned char scratch[ENERGON_STATIC_SCRATCH_BYTES];
+
+static int static_scratch(void** out) {
+  static std::mutex mu;
+  static void* addr[32] = {};
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 32) return ENERGON_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (addr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return ENERGON_ERR_HIP;
+    addr[dev] = p;
+  }
+  *out = addr[dev];
+  return ENERGON_OK;
+}
 
 extern "C" {
 
@@ -569,14 +594,16 @@ size_t energon_decode_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B) 
   return t ? t : 256;
 }
 
-int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y,
-                                 int32_t B, const int32_t* cache_lens_dev, const int32_t* cache_lens_host,
-                                 void* k_cache, void* v_cache, int32_t S_cap, void* ws, size_t ws_bytes,
-                                 void* stream) {
+// Validation and launches of one generation step's layer; `ws` is the caller's workspace or the
+// library's static scratch.
+static int decode_layer_checked(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y,
+                                int32_t B, const int32_t* cache_lens_dev, const int32_t* cache_lens_host,
+                                void* k_cache, void* v_cache, int32_t S_cap, void* ws, size_t ws_bytes,
+                                bool ws_is_static, void* stream) {
   int st = check_cfg(cfg);
   if (st != ENERGON_OK) return st;
   if (!is16(cfg->dtype)) return ENERGON_ERR_UNSUPPORTED;
-  if (!w || !x || !y || !cache_lens_dev || !k_cache || !v_cache || !ws) return ENERGON_ERR_NULL;
+  if (!w || !x || !y || !cache_lens_dev || !k_cache || !v_cache || (!ws && !ws_is_static)) return ENERGON_ERR_NULL;
   if (!w->ln1_g || !w->ln1_b || !w->w_qkv || !w->w_o || !w->ln2_g || !w->ln2_b || !w->w_fc1 || !w->w_fc2)
     return ENERGON_ERR_NULL;
   if (B < 0 || B > 65535 || S_cap <= 0) return ENERGON_ERR_SHAPE;
@@ -584,13 +611,17 @@ int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLay
   if (cache_lens_host)
     for (int32_t b = 0; b < B; ++b)
       if (cache_lens_host[b] < 0 || cache_lens_host[b] >= S_cap) return ENERGON_ERR_LENGTH;
-  const void* ptrs[] = {x, y, ws, k_cache, v_cache, w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o, w->b_o,
+  const void* ptrs[] = {x, y, k_cache, v_cache, w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o, w->b_o,
                         w->ln2_g, w->ln2_b, w->w_fc1, w->b_fc1, w->w_fc2, w->b_fc2};
   for (const void* p : ptrs)
     if (!aligned16(p)) return ENERGON_ERR_ALIGN;
-  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || (reinterpret_cast<uintptr_t>(cache_lens_dev) & 3u))
-    return ENERGON_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(cache_lens_dev) & 3u)) return ENERGON_ERR_ALIGN;
   if (ws_bytes < energon_decode_workspace_bytes(cfg, B)) return ENERGON_ERR_CAPACITY;
+  if (ws_is_static) {   // every argument has passed: now, and only now, touch the device
+    st = static_scratch(&ws);
+    if (st != ENERGON_OK) return st;
+  }
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return ENERGON_ERR_ALIGN;
   if (B == 0) return ENERGON_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const WsLayout l = ws_layout(cfg, B);
@@ -614,6 +645,22 @@ int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLay
   STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, B, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s, nullptr, part));
 #undef STEP
   return ENERGON_OK;
+}
+
+int energon_decode_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y,
+                                 int32_t B, const int32_t* cache_lens_dev, const int32_t* cache_lens_host,
+                                 void* k_cache, void* v_cache, int32_t S_cap, void* ws, size_t ws_bytes,
+                                 void* stream) {
+  return decode_layer_checked(cfg, w, x, y, B, cache_lens_dev, cache_lens_host, k_cache, v_cache, S_cap, ws, ws_bytes,
+                              false, stream);
+}
+
+int energon_decode_layer_forward_static(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x,
+                                        void* y, int32_t B, const int32_t* cache_lens_dev,
+                                        const int32_t* cache_lens_host, void* k_cache, void* v_cache, int32_t S_cap,
+                                        void* stream) {
+  return decode_layer_checked(cfg, w, x, y, B, cache_lens_dev, cache_lens_host, k_cache, v_cache, S_cap, nullptr,
+                              (size_t)ENERGON_STATIC_SCRATCH_BYTES, true, stream);
 }
 
 int energon_embed_packed(const int32_t* ids_dev, const int32_t* cu, int64_t T, int32_t B, const void* wte, int32_t V,
