@@ -15,6 +15,9 @@ the timed region.  Prints ONE JSON line:
   decode     one generation step (one new token per sequence on cached keys / values of the
              batch's lengths) through the same L layers: bound by streaming the weights and the
              cache from HBM once; algorithmic bytes / time against the HBM peak
+  other_workloads  the tensor-parallel shard and the heavy-padding workload (each packed and padded:
+             the speed-up against the row ratio) and the zero-padding control (whole step against the
+             layers alone: what pack + unpack cost when there is nothing to remove), a few steps each
   cpu_baseline  the CPU oracle timed on a bounded sample of whole sequences, one layer
 """
 import argparse
@@ -35,6 +38,81 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 GEMM_TRAFFIC_BYTES = {"gpt13b_bf16": 2722e6}
 
 
+def measure_other_workload(name, steps, warmup, seed, log):
+    """Packed and padded step of another workload (fewer steps than the headline): ms/step, effective
+    tokens/s per layer, algorithmic TFLOP/s, share of the bf16 MFMA peak, speed-up over the padded path
+    against the row ratio; for the padded run also the layers alone (no pack / unpack), which is the
+    zero-padding control: every length = S, packing is the identity permutation."""
+    import torch
+    from paper_2209_02341_amd import binding as E
+    from paper_2209_02341_amd import harness as hz
+    from paper_2209_02341_amd import workloads as wl
+
+    w = wl.WORKLOADS[name]
+    L, H, A, F, B, S = w.layers, w.hidden, w.attn_width, w.ffn, w.batch, w.max_len
+    lens = wl.sample_lengths(w, seed)
+    T = int(lens.sum())
+    x_dev = hz.to_device(wl.sample_x(w, seed), w.dtype)
+    dev_layers = [hz.DeviceLayer(wl.sample_layer(w, l, seed), w.dtype) for l in range(L)]
+    cfg = hz.layer_config(H, w.n_heads, w.head_dim, F, w.dtype, w.ln_eps)
+
+    def timed(fn, n, nwarm):
+        for _ in range(nwarm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    def flops(lengths):
+        t = float(lengths.sum())
+        return L * (t * (8.0 * H * A + 4.0 * H * F) + 2.0 * A * float(np.sum(lengths.astype(np.float64) * (lengths + 1))))
+
+    out = {"valid_tokens": T, "rows_padded": B * S, "rows_ratio": B * S / T}
+    run = hz.PackedRun(cfg, B, S, T)
+    ms = timed(lambda: run.forward(x_dev, lens, dev_layers), steps, warmup)
+    stage = {k: 0.0 for k in E.STAGE_NAMES}
+    src, dst = run.x_packed, run.y_packed
+    for layer in dev_layers:
+        for k, v in E.energon_layer_forward_profiled(cfg, layer.struct, src, dst, T, run.cu, lens, S, run.workspace).items():
+            stage[k] += v / L
+        src, dst = dst, src
+    tf = flops(lens) / (ms * 1e-3) / 1e12
+    out["packed"] = {"ms_per_step": ms, "value": T * L / (ms * 1e-3), "tflops": tf,
+                     "pct_bf16_mfma_peak": 100.0 * tf / PEAK_BF16_TFLOPS, "stage_ms_per_layer": stage}
+    del run
+    torch.cuda.empty_cache()
+    full = np.full(B, S, dtype=np.int32)
+    run_p = hz.PackedRun(cfg, B, S, B * S)
+    n_pad = max(2, steps // 2)
+    ms_pad = timed(lambda: run_p.forward(x_dev, full, dev_layers), n_pad, 1)
+
+    def layers_only():
+        src, bufs = x_dev.view(B * S, H), (run_p.y_packed, run_p.x_packed)
+        for i, layer in enumerate(dev_layers):
+            E.energon_layer_forward(cfg, layer.struct, src, bufs[i & 1], B * S, run_p.cu, full, S, run_p.workspace)
+            src = bufs[i & 1]
+
+    ms_layers = timed(layers_only, n_pad, 1)
+    tf_pad = flops(full) / (ms_pad * 1e-3) / 1e12
+    out["padded"] = {"ms_per_step": ms_pad, "value": T * L / (ms_pad * 1e-3),
+                     "speedup_packed_over_padded": ms_pad / ms}
+    out["zero_padding_control"] = {
+        "what": "every length = S: pack + layers + unpack against the layers alone on the padded tensor",
+        "ms_per_step": ms_pad, "ms_layers_only": ms_layers, "pack_unpack_share": (ms_pad - ms_layers) / ms_pad,
+        "tflops": tf_pad, "pct_bf16_mfma_peak": 100.0 * tf_pad / PEAK_BF16_TFLOPS}
+    log(f"[bench] {name}: T={T} of {B * S} rows; packed {ms:.3f} ms/step = {tf:.0f} TFLOP/s "
+        f"({100.0 * tf / PEAK_BF16_TFLOPS:.1f} %), padded {ms_pad:.3f} ms -> {ms_pad / ms:.2f}x at row ratio {B * S / T:.2f}; "
+        f"control: layers alone {ms_layers:.3f} ms, pack + unpack {100.0 * (ms_pad - ms_layers) / ms_pad:.2f} % of the step")
+    del run_p, x_dev, dev_layers
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +125,7 @@ def main():
     ap.add_argument("--no-paper-path", action="store_true")
     ap.add_argument("--no-ln-folded", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -256,6 +335,14 @@ def main():
         del run_p
         torch.cuda.empty_cache()
 
+    # ---- the other large workloads: tensor-parallel shard, heavy padding, zero-padding control ----
+    others = None
+    if not args.no_other_workloads and args.workload == "gpt13b_bf16":
+        del x_dev, dev_layers
+        torch.cuda.empty_cache()
+        others = {name: measure_other_workload(name, max(3, args.steps // 4), 2, args.seed, log)
+                  for name in ("gpt175b_tp8_shard_bf16", "heavy_pad_bf16")}
+
     # ---- CPU oracle on a bounded sample: whole sequences near the median length, one layer ----
     cpu = None
     if not args.no_cpu_baseline:
@@ -297,7 +384,8 @@ def main():
                      "flops_per_launch": gemm_flops_layer / 4},
         "stage_ms_per_layer": stage_ms, "stage_tflops": stage_tflops,
         "pack_ms": pack_ms, "unpack_ms": unpack_ms, "hbm": hbm,
-        "padded": padded, "paper_attention_path": paper_path, "ln_folded": ln_folded, "decode": decode, "cpu_baseline": cpu,
+        "padded": padded, "paper_attention_path": paper_path, "ln_folded": ln_folded, "decode": decode,
+        "other_workloads": others, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 

@@ -11,7 +11,10 @@
  *
  * Conventions for every entry point
  *   - Pointers named *_dev are DEVICE pointers, *_host are HOST pointers.  The caller
- *     owns every buffer; the library allocates nothing and keeps no state between calls.
+ *     owns every buffer; the library allocates nothing.  The only state it keeps between calls
+ *     is per device and set-once: a flag per kernel that its dynamic-LDS limit has been raised
+ *     on that device (first launch there), and the address of the fixed scratch array of
+ *     energon_decode_layer_forward_static (first call there).  No result depends on either.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued on it and the call returns without waiting; two calls on different
  *     streams may run concurrently if their buffers do not overlap.
@@ -116,7 +119,11 @@ int energon_workspace_layout(const EnergonLayerConfig* cfg, int64_t tokens, size
  * cu_seqlens_dev[B+1] (exclusive prefix sum of lengths, cu[B] = T) and gathers the valid
  * rows:  x_packed[cu[b]+s, :] = x_padded[b, s, :],  token_idx_dev[cu[b]+s] = b*S + s.
  *   x_padded_dev   [B, S, H]   in
- *   lengths_host   [B]         in, host; copied before return, reusable afterwards
+ *   lengths_host   [B]         in, host; copied before return, reusable afterwards.  Up to 896
+ *                              sequences: the lengths travel in the launch's argument block, the
+ *                              call is one kernel launch and never waits (capturable in a HIP
+ *                              graph, with these lengths baked in).  More: they are uploaded with a
+ *                              copy from pageable memory, which makes the call wait for `stream`.
  *   x_packed_dev   [capacity_tokens, H] out; rows >= T are left untouched
  *   cu_seqlens_dev [B+1] int32 out;  token_idx_dev [capacity_tokens] int32 out (first T)
  *   total_tokens_out           host, optional: T, computed on the host (no device sync)
@@ -143,7 +150,8 @@ int energon_unpack(const void* y_packed_dev, const int32_t* cu_seqlens_dev, int6
  *   shapes only: sum must equal T, each 0 <= len <= max_len);
  *   workspace_dev: at least energon_workspace_bytes(cfg, T) bytes, 256-byte aligned.
  * Errors: NULL, SHAPE (dims <= 0, H/A/F not multiples of 4 (bf16, fp16: of 64)),
- * LENGTH, CAPACITY (workspace), ALIGN, UNSUPPORTED (head_dim not 64/128, dtype), HIP. */
+ * LENGTH, CAPACITY (workspace), ALIGN, UNSUPPORTED (head_dim not 64/128, dtype, H > 32768
+ * (fp32: 16384), A or F >= 2^24), HIP. */
 int energon_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeights* weights,
                           const void* x_packed_dev, void* y_packed_dev, int64_t T,
                           const int32_t* cu_seqlens_dev, const int32_t* lengths_host, int32_t B,
@@ -171,7 +179,7 @@ int energon_layernorm(const void* x_dev, const void* gamma_dev, const void* beta
 /* y[M, N] = epilogue(x[M, K] W[N, K]^T + bias[N]) with residual r[M, N] for
  * ENERGON_EPI_BIAS_RESIDUAL (r may be the same buffer as y).  bias_dev may be NULL.
  * bf16 / fp16: MFMA, fp32 accumulation, epilogue in fp32, one rounding on store;
- * needs K % 64 == 0 and N % 8 == 0.  fp32: N % 4 == 0, K % 4 == 0. */
+ * needs K % 64 == 0 and N % 8 == 0.  fp32: N % 4 == 0, K % 4 == 0.  K < 2^24 (else UNSUPPORTED). */
 int energon_linear(const void* x_dev, const void* w_dev, const void* bias_dev,
                    const void* residual_dev, void* y_dev, int64_t M, int32_t N, int32_t K,
                    int32_t epilogue, int32_t dtype, void* stream);

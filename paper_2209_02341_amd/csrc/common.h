@@ -127,6 +127,13 @@ struct LnFold {
 
 // ---- launchers (each returns the hipError_t of its launch) --------------------------------
 // pack.hip
+// Up to kLensArgMax sequence lengths travel by value in the gather kernel's argument block (the
+// block is limited to 4 KiB), which then builds cu_seqlens itself: one launch, no copy.
+constexpr int kLensArgMax = 896;
+struct LensArg { int32_t v[kLensArgMax]; };
+hipError_t launch_pack_scan_rows(const void* x_padded, void* x_packed, const int32_t* lengths_host, int32_t* cu,
+                                 int32_t* token_idx, int32_t B, int32_t S, int64_t row_bytes, int64_t T,
+                                 hipStream_t s);
 hipError_t launch_scan_lengths(int32_t* cu_seqlens, int32_t B, hipStream_t s);
 hipError_t launch_pack_rows(const void* x_padded, void* x_packed, const int32_t* cu, int32_t* token_idx,
                             int32_t B, int32_t S, int64_t row_bytes, int64_t T, hipStream_t s);

@@ -14,6 +14,7 @@ inline int esize(int32_t dt) { return is16(dt) ? 2 : 4; }
 inline int vec_elems(int32_t dt) { return is16(dt) ? 8 : 4; }
 inline bool dtype_ok(int32_t dt) { return dt == ENERGON_F32 || dt == ENERGON_BF16 || dt == ENERGON_F16; }
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+constexpr int64_t kMaxReduction = (int64_t)1 << 24;   // K of a contraction: 32-bit byte offsets inside a tile
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ENERGON_ERR_HIP; } while (0)
 
 int check_cfg(const EnergonLayerConfig* c) {
@@ -22,7 +23,10 @@ int check_cfg(const EnergonLayerConfig* c) {
   if (c->hidden <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->ffn <= 0) return ENERGON_ERR_SHAPE;
   if (c->head_dim != 64 && c->head_dim != 128) return ENERGON_ERR_UNSUPPORTED;
   const int64_t A = (int64_t)c->n_heads * c->head_dim;
-  if (A > (1 << 28) || c->hidden > (1 << 28) || c->ffn > (1 << 28)) return ENERGON_ERR_SHAPE;
+  // LayerNorm keeps a row in the registers of one workgroup (256 threads x 16 vectors of 16 bytes);
+  // the contractions address a tile's rows with 32-bit byte offsets (128 rows x K x 2 bytes)
+  if (c->hidden > (is16(c->dtype) ? 32768 : 16384)) return ENERGON_ERR_UNSUPPORTED;
+  if (A >= kMaxReduction || c->ffn >= kMaxReduction) return ENERGON_ERR_UNSUPPORTED;
   // bf16 / fp16: every reduction dimension (H, A, F) is walked in 64-element slabs by the MFMA GEMM
   const int div = is16(c->dtype) ? 64 : 4;
   if (c->hidden % div || A % div || c->ffn % div) return ENERGON_ERR_SHAPE;
@@ -319,10 +323,17 @@ int energon_pack(const void* x_padded, const int32_t* lengths, int32_t B, int32_
       (reinterpret_cast<uintptr_t>(token_idx) & 3u))
     return ENERGON_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // lengths land in cu[1..B]; the scan kernel turns them into the prefix sums in place
-  HIP_TRY(hipMemcpyAsync(cu + 1, lengths, sizeof(int32_t) * (size_t)B, hipMemcpyHostToDevice, s));
-  HIP_TRY(launch_scan_lengths(cu, B, s));
-  HIP_TRY(launch_pack_rows(x_padded, x_packed, cu, token_idx, B, S, (int64_t)H * esize(dtype), T, s));
+  if (B <= kLensArgMax) {
+    // one launch: the lengths ride in the kernel's argument block (copied at launch, so the call
+    // neither waits for the stream nor reads lengths after it returns)
+    HIP_TRY(launch_pack_scan_rows(x_padded, x_packed, lengths, cu, token_idx, B, S, (int64_t)H * esize(dtype), T, s));
+  } else {
+    // lengths land in cu[1..B]; the scan kernel turns them into the prefix sums in place.  The copy
+    // from pageable host memory makes the runtime wait until the bytes have left the host buffer.
+    HIP_TRY(hipMemcpyAsync(cu + 1, lengths, sizeof(int32_t) * (size_t)B, hipMemcpyHostToDevice, s));
+    HIP_TRY(launch_scan_lengths(cu, B, s));
+    HIP_TRY(launch_pack_rows(x_padded, x_packed, cu, token_idx, B, S, (int64_t)H * esize(dtype), T, s));
+  }
   if (total_out) *total_out = T;
   return ENERGON_OK;
 }
@@ -434,6 +445,7 @@ int energon_linear(const void* x, const void* w, const void* bias, const void* r
   if (epilogue == ENERGON_EPI_BIAS_RESIDUAL && !residual) return ENERGON_ERR_NULL;
   if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0) return ENERGON_ERR_SHAPE;
   if (is16(dtype) ? (K % 64 != 0 || N % 8 != 0) : (K % 4 != 0 || N % 4 != 0)) return ENERGON_ERR_SHAPE;
+  if (K >= kMaxReduction) return ENERGON_ERR_UNSUPPORTED;
   if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(y))
     return ENERGON_ERR_ALIGN;
   return linear_impl(x, w, bias, residual, y, M, N, K, epilogue, dtype, static_cast<hipStream_t>(stream));
@@ -486,6 +498,7 @@ int energon_linear_ln_folded(const void* x, const void* w_folded, const float* c
   if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
   if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0) return ENERGON_ERR_SHAPE;
   if (K % 64 != 0 || N % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (K >= kMaxReduction) return ENERGON_ERR_UNSUPPORTED;
   if (!aligned16(x) || !aligned16(w_folded) || !aligned16(colsum) || !aligned16(bias_folded) || !aligned16(y) ||
       (reinterpret_cast<uintptr_t>(stats) & 7u))
     return ENERGON_ERR_ALIGN;
@@ -509,6 +522,7 @@ int energon_linear_residual_stats(const void* x, const void* w, const void* bias
   if (!is16(dtype)) return ENERGON_ERR_UNSUPPORTED;
   if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0 || !(eps >= 0.f)) return ENERGON_ERR_SHAPE;
   if (K % 64 != 0 || N % 8 != 0) return ENERGON_ERR_SHAPE;
+  if (K >= kMaxReduction) return ENERGON_ERR_UNSUPPORTED;
   if (N > 32768) return ENERGON_ERR_UNSUPPORTED;
   if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(y) ||
       (reinterpret_cast<uintptr_t>(stats_out) & 7u) || (reinterpret_cast<uintptr_t>(scratch) & 255u))

@@ -33,13 +33,6 @@ constexpr int kChunks = BK / 8;   // 16-byte chunks per LDS row
 constexpr int kXcds = 8;
 constexpr int kGroupM = 8;        // row tiles per band
 
-#ifdef ENERGON_GEMM_TIMING  // development aid, never defined in the library build
-__device__ long long* g_gemm_timing;
-#define ENERGON_STAMP(i) do { if (threadIdx.x == 0) g_gemm_timing[blockIdx.x * 4 + (i)] = wall_clock64(); } while (0)
-#else
-#define ENERGON_STAMP(i) do { } while (0)
-#endif
-
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -416,7 +409,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   // for the shared elements, so no load is clamped and no store is predicated.
   if (m0 > M - BM) m0 = M - BM;
   if (n0 > N - BN) n0 = N - BN;
-  ENERGON_STAMP(0);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
@@ -521,7 +513,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   ENERGON_RA(0, 0); ENERGON_RA(1, 0); ENERGON_RA(2, 0); ENERGON_RA(3, 0);
   ENERGON_RB(0, 0); ENERGON_RB(1, 0); ENERGON_RB(2, 0); ENERGON_RB(3, 0);
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  ENERGON_STAMP(1);
 
   // Slab kt is consumed from buffer kt & 1 while slab kt+1 (other buffer) is landing.  Quadrants
   // 2, 3, 4, 5 hold the last reads of the classes AL, BH, BL, AH of slab kt; the barrier that
@@ -586,12 +577,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
 
   // The epilogue's per-lane addresses must not be computed (and kept live) above the slab loop,
   // where every VGPR is spoken for: route the lane id through an ordered asm statement.
-  ENERGON_STAMP(2);
   int lane_e = lane;
   asm volatile("" : "+v"(lane_e));
   store_tile_coalesced(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
                        reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf);
-  ENERGON_STAMP(3);
 }
 
 template <typename E, typename Kern>

@@ -308,13 +308,4 @@ template hipError_t launch_gemm_skinny<bf16_t>(const bf16_t*, const bf16_t*, con
 template hipError_t launch_gemm_skinny<f16_t>(const f16_t*, const f16_t*, const f16_t*, const f16_t*, f16_t*, int64_t,
                                               int32_t, int32_t, int, hipStream_t, float*);
 
-#ifdef ENERGON_SKINNY_PROBE  // development aid, never defined in the library build
-hipError_t skinny_probe(const bf16_t* x, const bf16_t* w, bf16_t* y, float* partial, int nt, int ks, int32_t M, int32_t N,
-                        int32_t K, hipStream_t s) {
-  float* p = ks > 1 ? partial : nullptr;
-  return nt == 4 ? launch_nt<bf16_t, 4>(x, w, nullptr, nullptr, y, p, ks, M, N, K, 0, s)
-                 : launch_nt<bf16_t, 2>(x, w, nullptr, nullptr, y, p, ks, M, N, K, 0, s);
-}
-#endif
-
 }  // namespace energon

@@ -106,6 +106,12 @@ def test_layer_forward_rejects_bad_arguments():
     assert layer_status(T=6) == -3                 # lengths do not sum to T
     assert layer_status(lengths=(5, 0)) == -3      # longer than max_len
     assert layer_status(ws_bytes=1024) == -4
+    # limits of the kernels behind the call: a LayerNorm row must fit one workgroup's registers,
+    # a contraction addresses a tile's rows with 32-bit byte offsets
+    assert layer_status(c=cfg(hidden=32768 + 64, n_heads=513, head_dim=64)) == -6
+    assert layer_status(c=cfg(dtype=E.F32, hidden=16384 + 64, n_heads=257, head_dim=64)) == -6
+    assert layer_status(c=cfg(ffn=1 << 24)) == -6
+    assert layer_status(c=cfg(n_heads=1 << 18, head_dim=64, hidden=1024)) == -6
     assert layer_status(ws=FAKE + 16) == -5
     assert layer_status(y=FAKE + 2) == -5
     st = E.lib().energon_layer_forward_profiled
@@ -122,6 +128,7 @@ def test_stage_entry_points_reject_bad_arguments():
     assert l.energon_linear(FAKE, FAKE, None, None, FAKE, 4, 64, 64, E.EPI_BIAS_RESIDUAL, E.BF16, None) == -1
     assert l.energon_linear(FAKE, FAKE, None, None, FAKE, 4, 64, 96, E.EPI_BIAS, E.BF16, None) == -2
     assert l.energon_linear(FAKE, FAKE, None, None, FAKE, 4, 64, 64, 9, E.BF16, None) == -6
+    assert l.energon_linear(FAKE, FAKE, None, None, FAKE, 4, 64, 1 << 24, E.EPI_BIAS, E.BF16, None) == -6
     assert l.energon_linear(FAKE, FAKE, FAKE + 2, None, FAKE, 4, 64, 64, E.EPI_BIAS, E.BF16, None) == -5
     assert l.energon_attention(FAKE, FAKE, FAKE, 5, 2, 4, 2, 32, E.BF16, None) == -6
     assert l.energon_attention(FAKE, None, FAKE, 5, 2, 4, 2, 64, E.BF16, None) == -1
@@ -239,3 +246,19 @@ def test_cache_fill_and_embed_at_reject_bad_arguments():
     assert e(FAKE, FAKE, 4, FAKE, 100, FAKE, 16, 60, E.BF16, FAKE, None) == -2
     assert e(FAKE, FAKE, 4, FAKE, 100, FAKE, 16, 64, E.F32, FAKE, None) == -6
     assert e(FAKE, FAKE, 0, FAKE, 100, FAKE, 16, 64, E.BF16, FAKE, None) == 0
+
+
+def test_static_scratch_generation_step_rejects_bad_arguments_before_touching_the_device():
+    f = E.lib().energon_decode_layer_forward_static
+    c, w = cfg(), E.LayerWeights(*([FAKE] * 12))
+    lens = np.asarray([3, 2], dtype=np.int32)
+    ok_args = lambda **kw: [kw.get("c", C.byref(c)), C.byref(w), kw.get("x", FAKE), kw.get("y", FAKE + 4096), kw.get("B", 2),
+                            FAKE, kw.get("lens", lens.ctypes.data), FAKE, FAKE, kw.get("S_cap", 8), None]
+    assert f(*ok_args(x=None)) == -1
+    assert f(*ok_args(y=FAKE)) == -6                      # x and y may not alias
+    assert f(*ok_args(S_cap=0)) == -2
+    assert f(*ok_args(S_cap=3)) == -3                     # a cached length that does not fit the cache
+    assert f(*ok_args(x=FAKE + 2)) == -5
+    assert f(*ok_args(B=60000, lens=None)) == -4          # beyond the fixed scratch array
+    c32 = cfg(dtype=E.F32)
+    assert f(*ok_args(c=C.byref(c32))) == -6

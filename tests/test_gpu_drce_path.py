@@ -9,7 +9,7 @@ from oracle import energon_oracle as orc
 from paper_2209_02341_amd import binding as E
 from paper_2209_02341_amd import harness as hz
 from paper_2209_02341_amd import workloads as wl
-from test_gpu_parity import assert_close
+from test_gpu_parity import assert_close, layer_noise, recipe_logit_rms
 
 pytestmark = pytest.mark.gpu
 
@@ -62,7 +62,7 @@ def test_padded_attention_core(lengths, S, nh, d, dtype):
     E.energon_attention_padded(qd, kd, vd, cud, od)
     got = hz.to_host(od)
     ref = orc.padded_attention_heads(q, k, v, lens)
-    assert_close(got, ref, dtype, "padded attention")   # all S positions, pad queries included
+    assert_close(got, ref, dtype, "padded attention", stages=2)   # all S positions, pad queries included
     for b in range(B):
         if lens[b] == 0:
             assert not got[b].any()
@@ -88,5 +88,8 @@ def test_drce_layer_equals_oracle_and_variable_length_layer(name):
     E.energon_layer_forward_drce(cfg, layer.struct, run.x_packed, run.y_packed, T, run.cu, lens, S, run.workspace, padws)
     torch.cuda.synchronize()
     ref = orc.pack(orc.stack_forward(x, lens, layers, w.n_heads, w.head_dim, w.ln_eps), lens)
-    assert_close(hz.to_host(run.y_packed), ref, w.dtype, "drce layer vs oracle")
-    assert_close(hz.to_host(run.y_packed), hz.to_host(y_var).astype(np.float64), w.dtype, "drce vs variable-length", tol=4e-3 if w.dtype == wl.BF16 else 1e-3)
+    noise = layer_noise(1, recipe_logit_rms(w.hidden))
+    assert_close(hz.to_host(run.y_packed), ref, w.dtype, "drce layer vs oracle", **noise)
+    # two GPU results that share everything up to the attention stage: its two roundings and the four stages after it, twice
+    assert_close(hz.to_host(run.y_packed), hz.to_host(y_var).astype(np.float64), w.dtype, "drce vs variable-length",
+                 tol=4e-3 if w.dtype == wl.BF16 else 1e-3, stages=12)

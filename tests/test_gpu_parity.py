@@ -1,14 +1,31 @@
 """GPU parity: every stage and the whole pack -> layers -> unpack path, called through the
 C ABI, against the CPU fp64 oracle on the same seeded inputs.
 
-Bars: integer / byte work (compaction indices, gathered and scattered rows, zero fill) is
-bit-exact.  Floating point: max|gpu - oracle| / max|oracle| <= 1e-2 per tensor for bf16
-storage (fp32 accumulation; one bf16 rounding per stage boundary, 2^-9 relative each),
-<= 2.5e-3 for fp16 storage (2^-11 per rounding, the same factor above it) and <= 1e-4 for fp32 storage; plus, so that one wrong row cannot hide behind larger rows,
-elementwise |gpu - oracle| <= tol*|oracle| + 2*tol*max|oracle row|.  (The factor 2 is needed by
-the hidden-12288 workload: its logits have a standard deviation near 5, so the bf16 rounding of q
-and k, 2^-9 relative each, moves individual attention weights by 1-2 %.)
+Bars.  Integer / byte work (compaction indices, gathered and scattered rows, zero fill) is
+bit-exact.  Floating point, per compared tensor:
+
+  primary   max|gpu - oracle| <= tol * max|oracle|, tol = 1e-2 for bf16 storage (the stated bar),
+            2.5e-3 for fp16 (unit roundoff 2^-11 instead of 2^-9) and 1e-4 for fp32 storage;
+  guard     elementwise, so that one wrong row cannot hide behind larger rows:
+            |gpu - oracle| <= tol * |oracle| + 7 * sigma * rms(oracle row),
+            sigma = u / sqrt(3) * sqrt(n + 2 * a * s^2).
+
+The guard's second term is seven standard deviations of the rounding noise that the arithmetic
+itself predicts.  u is the unit roundoff of the storage type (2^-9 bf16, 2^-11 fp16): each of the n
+stage outputs between the exact inputs and the compared tensor is rounded once to storage, a
+uniform relative error of standard deviation u / sqrt(3) per element; through a contraction with
+zero-mean terms such errors reach the next stage's row with the same standard deviation relative to
+that row's rms, and independent stages add in quadrature.  Attention amplifies what it receives:
+the rounding of q and k moves a logit of standard deviation s by sqrt(2/3) u s, the softmax weight
+by the same relative amount, the output row by sqrt(2) s times the per-stage figure: 2 s^2 more
+"stages" for each of the a attention stages upstream.  Seven sigma leaves the expected number of
+false alarms over all elements compared in this suite (about 1e9) below 1e-2.  For fp32 storage the
+same form is used with sigma = 1.5e-5 sqrt(n) (accumulation order over K <= 16384 terms, the hardware
+exp2 / rsqrt, the fitted erfc).  Every comparison appends its two margins (worst error / bound) to
+MARGINS; tests/conftest.py writes them out at the end of a GPU session.
 """
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -21,9 +38,49 @@ from paper_2209_02341_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 TOL = {wl.BF16: 1e-2, wl.F16: 2.5e-3, wl.F32: 1e-4}
+UNIT = {wl.BF16: 2.0 ** -9, wl.F16: 2.0 ** -11}
+K_SIGMA = 7.0
+MARGINS = []   # (what, dtype, primary margin, guard margin) of every comparison made so far
+# rounded stage outputs from a layer's input up to and including each tensor of one layer
+STAGES = {"u": 1, "qkv": 2, "attn": 3, "y1": 4, "w": 5, "m": 6, "y": 7}
+AFTER_ATTENTION = ("attn", "y1", "w", "m", "y")
 
 
-def assert_close(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str, tol=None):
+def rel_sigma(dtype: str, stages: float, logit_rms: float = 0.0, attn_stages: int = 0) -> float:
+    """Predicted standard deviation of the rounding noise, relative to the rms of a row (see above)."""
+    if dtype == wl.F32:
+        return 1.5e-5 * math.sqrt(stages)
+    return UNIT[dtype] / math.sqrt(3.0) * math.sqrt(stages + 2.0 * attn_stages * logit_rms ** 2)
+
+
+def logit_rms_of(x_seq, p, n_heads, head_dim, eps=1e-5) -> float:
+    """rms of the causal attention logits q.k / sqrt(d) of one sequence in one layer (oracle arithmetic)."""
+    A = n_heads * head_dim
+    u = orc.layer_norm(np.asarray(x_seq, dtype=np.float64), p["ln1_g"].astype(np.float64), p["ln1_b"].astype(np.float64), eps)
+    qkv = orc.linear(u, p["w_qkv"].astype(np.float64), None if p["b_qkv"] is None else p["b_qkv"].astype(np.float64))
+    n = qkv.shape[0]
+    q = qkv[:, :A].reshape(n, n_heads, head_dim)
+    k = qkv[:, A:2 * A].reshape(n, n_heads, head_dim)
+    s = np.einsum("ihc,jhc->hij", q, k) / math.sqrt(head_dim)
+    tri = np.tril(np.ones((n, n), dtype=bool))
+    return float(np.sqrt(np.mean(s[:, tri] ** 2)))
+
+
+def recipe_logit_rms(hidden: int, std: float = 0.02) -> float:
+    """rms of the logits for weights ~ N(0, std) behind a LayerNorm of unit gain: q and k components
+    have rms sqrt(hidden) * std, and the d products of a logit, divided by sqrt(d), keep that product."""
+    return hidden * std * std
+
+
+def layer_noise(n_layers: int, logit_rms: float) -> dict:
+    """assert_close's noise arguments for the output of n_layers whole layers."""
+    return dict(stages=7 * n_layers, logit_rms=logit_rms, attn_stages=n_layers)
+
+
+def assert_close(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str, tol=None, stages: float = 1,
+                 logit_rms: float = 0.0, attn_stages: int = 0):
+    """stages / logit_rms / attn_stages: see rel_sigma.  `tol` replaces the primary bar (used only where
+    a comment derives the other value)."""
     tol = tol or TOL[dtype]
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     if ref.size == 0:
@@ -31,13 +88,18 @@ def assert_close(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str, tol=No
     assert np.all(np.isfinite(gpu)), what
     err = np.abs(gpu - ref)
     scale = np.abs(ref).max()
+    rows = ref.reshape(-1, ref.shape[-1])
+    row_rms = np.sqrt(np.mean(rows ** 2, axis=1)).reshape(ref.shape[:-1] + (1,))
+    bound = tol * np.abs(ref) + K_SIGMA * rel_sigma(dtype, stages, logit_rms, attn_stages) * row_rms
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(err > 0, err / bound, 0.0)
+    MARGINS.append((what, dtype, float(err.max() / (tol * scale)) if scale > 0 else 0.0, float(ratio.max())))
     assert err.max() <= tol * scale, f"{what}: max err {err.max():.3e} vs scale {scale:.3e}"
-    row_scale = np.abs(ref).reshape(-1, ref.shape[-1]).max(axis=1).reshape(ref.shape[:-1] + (1,))
-    bad = err > tol * np.abs(ref) + 2 * tol * row_scale
+    bad = err > bound
     if bad.any():
         worst = np.argwhere(bad)[:5]
         detail = "; ".join(f"{tuple(int(v) for v in i)}: gpu {gpu[tuple(i)]:.5g} ref {ref[tuple(i)]:.5g}" for i in worst)
-        raise AssertionError(f"{what}: {bad.sum()} elements outside tol, worst {err[bad].max():.3e} [{detail}]")
+        raise AssertionError(f"{what}: {bad.sum()} elements outside the guard, worst {ratio.max():.2f} x bound [{detail}]")
 
 
 def tdtype(dtype):
@@ -55,6 +117,11 @@ PACK_CASES = [
     (130, 3, 64, None, wl.BF16),        # more sequences than one wavefront scans at once
     (32, 512, 5120, None, wl.BF16),     # the 13B-shape batch
     (6, 40, 136, None, wl.F16),
+    (896, 3, 64, None, wl.BF16),        # the most sequences whose lengths travel in the launch's arguments
+    (897, 3, 64, None, wl.BF16),        # one more: lengths uploaded, scanned by a kernel of their own
+    (2500, 2, 8, None, wl.F32),
+    (33, 700, 5120, None, wl.BF16),     # rows in batches of eight vectors per lane plus a tail (640 = 10 per lane)
+    (3, 11, 4104, None, wl.BF16),       # 513 vectors per row: one full batch, one single
 ]
 
 
@@ -203,7 +270,7 @@ def test_attention(lengths, nh, d, dtype):
             continue
         blk = q64[s0:s1]
         ref = orc.masked_causal_attention(blk[:, :A], blk[:, A:2 * A], blk[:, 2 * A:], int(lens[b]), nh, d)
-        assert_close(out[s0:s1], ref, dtype, f"attention seq {b}")
+        assert_close(out[s0:s1], ref, dtype, f"attention seq {b}", stages=2)   # P, then the output
 
 
 # ------------------------------------------------------------------ whole path
@@ -230,13 +297,17 @@ def test_layer_forward_matches_oracle_with_intermediates(name):
     ref = orc.stack_forward(x, lens, layers, w.n_heads, w.head_dim, w.ln_eps, stages=st)
     out = hz.to_host(y)
     A = w.attn_width
+    b_long = int(np.argmax(lens))
+    s_rms = logit_rms_of(x[b_long, :lens[b_long]], layers[0], w.n_heads, w.head_dim, w.ln_eps)
     for key, which, cols in (("u", E.WS_U, w.hidden), ("qkv", E.WS_QKV, 3 * A), ("attn", E.WS_ATTN, A),
                              ("y1", E.WS_Y1, w.hidden), ("w", E.WS_W, w.hidden), ("m", E.WS_M, w.ffn)):
         got = hz.to_host(run.stage(which, cols))
-        assert_close(got, orc.pack(st[key], lens), w.dtype, f"{name} stage {key}")
+        assert_close(got, orc.pack(st[key], lens), w.dtype, f"{name} stage {key}", stages=STAGES[key],
+                     logit_rms=s_rms, attn_stages=int(key in AFTER_ATTENTION))
     for b in range(w.batch):
         assert np.all(out[b, lens[b]:] == 0)
-    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, f"{name} output")
+    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, f"{name} output", stages=7, logit_rms=s_rms,
+                 attn_stages=1)
 
 
 def test_padding_content_never_read_bitwise():
@@ -257,7 +328,9 @@ def test_padded_path_agrees_with_packed_path():
     full = np.full(w.batch, w.max_len, dtype=np.int32)
     _, y_padded = run_gpu(w, x, full, layers)
     a, b = hz.to_host(y_packed), hz.to_host(y_padded)
-    assert_close(orc.pack(b, lens), orc.pack(a, lens), w.dtype, "padded vs packed", tol=4e-3)
+    # two GPU runs of the same 7-stage chain whose contractions sum in different tile positions
+    assert_close(orc.pack(b, lens), orc.pack(a, lens), w.dtype, "padded vs packed", tol=4e-3, stages=14, logit_rms=1.0,
+                 attn_stages=2)
 
 
 def test_two_layer_stack_medium_shape():
@@ -268,7 +341,9 @@ def test_two_layer_stack_medium_shape():
     ref = orc.stack_forward(x, lens, layers, w.n_heads, w.head_dim, w.ln_eps)
     out = hz.to_host(y)
     assert np.all(out[1] == 0)
-    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, "two-layer stack")
+    s_rms = logit_rms_of(x[0, :96], layers[0], w.n_heads, w.head_dim, w.ln_eps)
+    assert_close(orc.pack(out, lens), orc.pack(ref, lens), w.dtype, "two-layer stack", stages=14, logit_rms=s_rms,
+                 attn_stages=2)
 
 
 def test_empty_batch_is_legal():
@@ -278,39 +353,83 @@ def test_empty_batch_is_legal():
     assert torch.count_nonzero(y.float()).item() == 0
 
 
-@pytest.mark.timeout(600)
+# ------------------------------------------------------------------ the large workloads at full size
+def check_full_shape_contractions(w: wl.Workload, M: int, layer: hz.DeviceLayer, params: dict, rows_per_block: int = 128):
+    """The four contractions of a layer at their real M x N x K, with the epilogue each has in the layer,
+    each on its own through energon_linear: one seeded row out of every block of `rows_per_block` rows
+    (so every row tile of every kernel that may take the shape is hit), plus the last row and the first
+    row of a last 256-row tile shifted inwards, all N columns, against the oracle's linear (+ GeLU /
+    + residual) on exactly those rows."""
+    H, A, F = w.hidden, w.attn_width, w.ffn
+    tdt = tdtype(w.dtype)
+    rng = np.random.default_rng(M + H)
+    starts = np.arange(0, M, rows_per_block)
+    rows = np.unique(np.concatenate([np.minimum(starts + rng.integers(0, rows_per_block, len(starts)), M - 1),
+                                     [M - 1, max(M - 256, 0), 0]])).astype(np.int64)
+    rows_d = torch.from_numpy(rows).cuda()
+    gen = torch.Generator(device="cuda").manual_seed(1234 + M)
+    for name, wkey, bkey, N, K, epi in (("qkv", "w_qkv", "b_qkv", 3 * A, H, E.EPI_BIAS),
+                                        ("out-proj", "w_o", "b_o", H, A, E.EPI_BIAS_RESIDUAL),
+                                        ("fc1", "w_fc1", "b_fc1", F, H, E.EPI_BIAS_GELU),
+                                        ("fc2", "w_fc2", "b_fc2", H, F, E.EPI_BIAS_RESIDUAL)):
+        xd = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.float32).to(tdt)
+        rd = torch.randn((M, N), generator=gen, device="cuda", dtype=torch.float32).to(tdt) if epi == E.EPI_BIAS_RESIDUAL else None
+        yd = torch.empty((M, N), dtype=tdt, device="cuda")
+        E.energon_linear(xd, layer.tensors[wkey], layer.tensors.get(bkey), rd, yd, epi)
+        got = hz.to_host(yd[rows_d])
+        x_rows = hz.to_host(xd[rows_d])
+        bias = params.get(bkey)
+        ref = orc.linear(x_rows, params[wkey].astype(np.float64), None if bias is None else bias.astype(np.float64))
+        if epi == E.EPI_BIAS_GELU:
+            ref = orc.gelu(ref)
+        if epi == E.EPI_BIAS_RESIDUAL:
+            ref = ref + hz.to_host(rd[rows_d])
+        assert_close(got, ref, w.dtype, f"{w.name} {name} {M}x{N}x{K}, {len(rows)} sampled rows")
+        del xd, rd, yd
+
+
+def sampled_check(w, lens, x, layers, y, picks, what, prefix=None):
+    """Oracle on the whole sequences `picks`, one at a time (or, with `prefix`, on their first `prefix`
+    tokens: the block is causal, so a prefix of a sequence is itself a valid shorter sequence)."""
+    L = len(layers)
+    for b in picks:
+        n = int(lens[b]) if prefix is None else min(int(lens[b]), prefix)
+        if n == 0:
+            continue
+        sub_len = np.array([n], dtype=np.int32)
+        ref = orc.stack_forward(x[b:b + 1, :n], sub_len, layers, w.n_heads, w.head_dim, w.ln_eps)
+        out = hz.to_host(y[int(b), :n])
+        s_rms = logit_rms_of(x[b, :n], layers[0], w.n_heads, w.head_dim, w.ln_eps)
+        assert_close(out, ref[0], w.dtype, f"{what}: sequence {int(b)} ({n} tokens)", stages=7 * L, logit_rms=s_rms,
+                     attn_stages=L)
+
+
+def zero_pads_nonzero_valid(y, lens):
+    yz = y.float().abs().sum(dim=2).cpu().numpy()
+    for b in range(len(lens)):
+        assert np.all(yz[b, lens[b]:] == 0) and np.all(yz[b, :lens[b]] > 0)
+
+
+@pytest.mark.timeout(900)
 def test_full_size_13b_shape_sampled_sequences():
-    """The benchmark's workload at full size (T ~ 8.7k rows, 4 layers of hidden 5120): the
-    oracle follows the two shortest sequences through the whole stack; sequences are
-    independent, so their rows must match the full-batch GPU run."""
+    """The benchmark's workload at full size (T ~ 8.4k rows, 4 layers of hidden 5120): the oracle follows
+    the two shortest sequences, the one nearest the median length and the longest one (512 tokens: four
+    query blocks of the attention kernel, rows in the deep row tiles of every contraction) through the
+    whole stack; sequences are independent, so their rows must match the full-batch GPU run."""
     w = wl.WORKLOADS["gpt13b_bf16"]
     lens = wl.sample_lengths(w)
     x = wl.sample_x(w)
     layers = [wl.sample_layer(w, l) for l in range(w.layers)]
-    _, y = run_gpu(w, x, lens, layers)
-    picks = np.argsort(lens)[:2]
-    out = hz.to_host(y[torch.from_numpy(picks).cuda()])
-    sub_len = lens[picks]
-    S_sub = int(sub_len.max())
-    ref = orc.stack_forward(x[picks][:, :S_sub], sub_len, layers, w.n_heads, w.head_dim, w.ln_eps)
-    assert_close(orc.pack(out[:, :S_sub], sub_len), orc.pack(ref, sub_len), w.dtype, "13B-shape sampled sequences")
-    assert np.all(out[0, sub_len[0]:] == 0)
-    # pad rows of the whole output are zero, valid rows are not
-    yz = y.float().abs().sum(dim=2).cpu().numpy()
-    for b in range(w.batch):
-        assert np.all(yz[b, lens[b]:] == 0) and np.all(yz[b, :lens[b]] > 0)
-
-
-# ------------------------------------------------------------------ the large workloads at full size
-def sampled_check(w, lens, x, layers, y, picks, what, prefix=None):
-    """Oracle on whole sequences `picks` (or, with `prefix`, on their first `prefix` tokens: the block
-    is causal, so a prefix of a sequence is itself a valid shorter sequence)."""
-    sub_len = lens[picks] if prefix is None else np.minimum(lens[picks], prefix).astype(np.int32)
-    s_sub = int(sub_len.max())
-    ref = orc.stack_forward(x[picks][:, :s_sub], sub_len, layers, w.n_heads, w.head_dim, w.ln_eps)
-    out = hz.to_host(y[torch.from_numpy(np.asarray(picks)).cuda()][:, :s_sub])
-    out = orc.zero_pad_rows(out, sub_len)
-    assert_close(orc.pack(out, sub_len), orc.pack(ref, sub_len), w.dtype, what)
+    cfg = hz.layer_config(w.hidden, w.n_heads, w.head_dim, w.ffn, w.dtype, w.ln_eps)
+    dev_layers = [hz.DeviceLayer(p, w.dtype) for p in layers]
+    run = hz.PackedRun(cfg, w.batch, w.max_len, int(lens.sum()))
+    y = run.forward(hz.to_device(x, w.dtype), lens, dev_layers)
+    torch.cuda.synchronize()
+    order = np.argsort(lens)
+    picks = [int(order[0]), int(order[1]), int(order[len(order) // 2]), int(order[-1])]
+    sampled_check(w, lens, x, layers, y, picks, "13B-shape stack")
+    zero_pads_nonzero_valid(y, lens)
+    check_full_shape_contractions(w, run.T, dev_layers[0], layers[0])
 
 
 @pytest.mark.timeout(900)
@@ -320,13 +439,17 @@ def test_full_size_tp_shard_sampled_sequences():
     w = wl.WORKLOADS["gpt175b_tp8_shard_bf16"]
     lens, x, layers = wl.sample_lengths(w), wl.sample_x(w), [wl.sample_layer(w, 0)]
     assert layers[0]["b_o"] is None and layers[0]["b_fc2"] is None
-    _, y = run_gpu(w, x, lens, layers)
+    cfg = hz.layer_config(w.hidden, w.n_heads, w.head_dim, w.ffn, w.dtype, w.ln_eps)
+    dev_layers = [hz.DeviceLayer(p, w.dtype) for p in layers]
+    run = hz.PackedRun(cfg, w.batch, w.max_len, int(lens.sum()))
+    y = run.forward(hz.to_device(x, w.dtype), lens, dev_layers)
+    torch.cuda.synchronize()
     order = np.argsort(lens)
-    sampled_check(w, lens, x, layers, y, order[:2], "TP shard, two shortest sequences")
-    sampled_check(w, lens, x, layers, y, order[-1:], "TP shard, prefix of the longest sequence", prefix=40)
-    yz = y.float().abs().sum(dim=2).cpu().numpy()
-    for b in range(w.batch):
-        assert np.all(yz[b, lens[b]:] == 0) and np.all(yz[b, :lens[b]] > 0)
+    sampled_check(w, lens, x, layers, y, [order[0], order[1], order[len(order) // 2]],
+                  "TP shard, two shortest sequences and the median one")
+    sampled_check(w, lens, x, layers, y, order[-1:], "TP shard, prefix of the longest sequence", prefix=300)
+    zero_pads_nonzero_valid(y, lens)
+    check_full_shape_contractions(w, run.T, dev_layers[0], layers[0])
 
 
 @pytest.mark.timeout(1500)
@@ -345,11 +468,11 @@ def test_full_size_heavy_padding_and_zero_padding_control():
     cu_ref, idx_ref = orc.pack_indices(lens, w.max_len)
     assert np.array_equal(run.cu.cpu().numpy(), cu_ref) and np.array_equal(run.idx.cpu().numpy()[:run.T], idx_ref)
     order = np.argsort(lens)
-    sampled_check(w, lens, x, layers, y, order[:3], "heavy padding, three shortest sequences")
-    sampled_check(w, lens, x, layers, y, order[-1:], "heavy padding, prefix of the longest", prefix=24)
-    yz = y.float().abs().sum(dim=2).cpu().numpy()
-    for b in range(w.batch):
-        assert np.all(yz[b, lens[b]:] == 0) and np.all(yz[b, :lens[b]] > 0)
+    sampled_check(w, lens, x, layers, y, [order[0], order[1], order[2], order[len(order) // 2]],
+                  "heavy padding, three shortest sequences and the median one")
+    sampled_check(w, lens, x, layers, y, order[-1:], "heavy padding, prefix of the longest", prefix=160)
+    zero_pads_nonzero_valid(y, lens)
+    check_full_shape_contractions(w, run.T, dev_layers[0], layers[0])
     y_first = y[int(order[-1]), :24].clone()
     del run, y
     torch.cuda.empty_cache()
@@ -361,7 +484,10 @@ def test_full_size_heavy_padding_and_zero_padding_control():
     assert run.T == w.batch * w.max_len
     assert np.array_equal(run.idx.cpu().numpy(), np.arange(w.batch * w.max_len, dtype=np.int32))
     assert torch.equal(run.x_packed.view(-1).view(torch.int16), xd.view(-1).view(torch.int16))
-    sampled_check(w, full, x, layers, y, [0, 63], "control, prefixes of two sequences", prefix=24)
+    sampled_check(w, full, x, layers, y, [0, 63], "control, prefixes of two sequences", prefix=160)
     # a causal block: the first 24 rows of a sequence do not depend on how long the sequence is
     assert torch.equal(y[int(order[-1]), :24].view(torch.int16), y_first.view(torch.int16))
     assert torch.isfinite(y.float()).all()
+    del run, y
+    torch.cuda.empty_cache()
+    check_full_shape_contractions(w, w.batch * w.max_len, dev_layers[0], layers[0], rows_per_block=256)

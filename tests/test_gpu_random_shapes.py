@@ -9,7 +9,7 @@ from oracle import energon_oracle as orc
 from paper_2209_02341_amd import binding as E
 from paper_2209_02341_amd import harness as hz
 from paper_2209_02341_amd import workloads as wl
-from test_gpu_parity import assert_close
+from test_gpu_parity import K_SIGMA, TOL, assert_close, layer_noise, logit_rms_of, rel_sigma
 
 pytestmark = pytest.mark.gpu
 
@@ -75,7 +75,7 @@ def test_attention_random_lengths(lens, nh, d, dtype):
         blk = qkv[s0:s0 + n].astype(np.float64)
         if n:
             ref = orc.masked_causal_attention(blk[:, :A], blk[:, A:2 * A], blk[:, 2 * A:], n, nh, d)
-            assert_close(got[s0:s0 + n], ref, dtype, f"attention seq {b} of {lens}")
+            assert_close(got[s0:s0 + n], ref, dtype, f"attention seq {b} of {lens}", stages=2)
         s0 += n
     assert np.all(got[T] == 3.0)
 
@@ -134,19 +134,27 @@ def test_layer_paths_random_config(H, nh, d, F, S, lens, dtype):
     w = wl.Workload("rand", dtype, 1, H, nh, d, F, B, S, "uniform", 0, S)
     rng = np.random.default_rng(H + F + S)
     x = wl.round_to_dtype(rng.standard_normal((B, S + 1, H)), dtype)     # one extra token per sequence for the step
-    # weight scale 0.05 keeps the attention logits at a standard deviation of 1-2: at 0.1 they reach 5-6
-    # and the 2^-9 rounding of q and k alone moves attention weights by more than the bf16 tolerance
-    p = wl.random_small_layer(rng, H, nh, d, F, dtype=dtype, std=0.05)
+    # Weights three times (odd cases: five times) the recipe's scale: the logits reach a standard deviation of
+    # several units, where the rounding of q and k alone moves the attention weights by per cent.  The
+    # bars follow the logit scale instead of the inputs being tamed: the guard through its noise model,
+    # the primary bar as max(stated tolerance, seven predicted standard deviations of a row's rms; a row's
+    # largest element is at least its rms).
+    std = 0.1 if (H + F + S) % 2 else 0.06
+    p = wl.random_small_layer(rng, H, nh, d, F, dtype=dtype, std=std)
     A = nh * d
     st = {}
     ref = orc.stack_forward(x[:, :S], lens, [p], nh, d, w.ln_eps, stages=st)
+    b_long = int(np.argmax(lens))
+    s_rms = logit_rms_of(x[b_long, :max(int(lens[b_long]), 1)], p, nh, d, w.ln_eps)
+    noise = layer_noise(1, s_rms)
+    noise["tol"] = max(TOL[dtype], K_SIGMA * rel_sigma(dtype, **noise))
     cfg = hz.layer_config(H, nh, d, F, dtype, w.ln_eps)
     layer = hz.DeviceLayer(p, dtype)
     T = int(lens.sum())
     run = hz.PackedRun(cfg, B, S, T)
     xd = hz.to_device(x[:, :S].copy(), dtype)
     y = hz.to_host(run.forward(xd, lens, [layer]).clone())
-    assert_close(orc.pack(y, lens), orc.pack(ref, lens), dtype, "plain path")
+    assert_close(orc.pack(y, lens), orc.pack(ref, lens), dtype, "plain path", **noise)
     # caches from this prefill's QKV stage, then one step with the extra token
     S_cap = S + 1
     kc = torch.zeros((B, S_cap, A), dtype=xd.dtype, device="cuda")
@@ -154,13 +162,13 @@ def test_layer_paths_random_config(H, nh, d, F, S, lens, dtype):
     if T:
         E.energon_cache_fill(run.stage(E.WS_QKV, 3 * A), run.cu, kc, vc)
     y_fold = hz.to_host(run.forward_folded(xd, lens, [hz.FoldedDeviceLayer(layer)]).clone())
-    assert_close(orc.pack(y_fold, lens), orc.pack(ref, lens), dtype, "folded path")
+    assert_close(orc.pack(y_fold, lens), orc.pack(ref, lens), dtype, "folded path", **noise)
     if T:
         padws = torch.empty(E.energon_drce_workspace_bytes(cfg, B, S), dtype=torch.uint8, device="cuda")
         yp = torch.empty_like(run.x_packed)
         E.energon_pack(xd, lens, run.x_packed, run.cu, run.idx)
         E.energon_layer_forward_drce(cfg, layer.struct, run.x_packed, yp, T, run.cu, lens, S, run.workspace, padws)
-        assert_close(hz.to_host(yp[:T]), orc.pack(ref, lens), dtype, "paper's attention path")
+        assert_close(hz.to_host(yp[:T]), orc.pack(ref, lens), dtype, "paper's attention path", **noise)
     x_new = np.stack([x[b, lens[b]] for b in range(B)])
     ref_step = orc.layer_forward_padded(x, lens + 1, p, nh, d, w.ln_eps)
     want = np.stack([ref_step[b, lens[b]] for b in range(B)])
@@ -168,4 +176,4 @@ def test_layer_paths_random_config(H, nh, d, F, S, lens, dtype):
     yn = torch.empty_like(xn)
     dws = torch.empty(E.energon_decode_workspace_bytes(cfg, B), dtype=torch.uint8, device="cuda")
     E.energon_decode_layer_forward(cfg, layer.struct, xn, yn, torch.tensor(lens, device="cuda"), lens, kc, vc, dws)
-    assert_close(hz.to_host(yn), want, dtype, "generation step after the prefill")
+    assert_close(hz.to_host(yn), want, dtype, "generation step after the prefill", **noise)
