@@ -385,6 +385,7 @@ def check_full_shape_contractions(w: wl.Workload, M: int, layer: hz.DeviceLayer,
         if epi == E.EPI_BIAS_RESIDUAL:
             ref = ref + hz.to_host(rd[rows_d])
         assert_close(got, ref, w.dtype, f"{w.name} {name} {M}x{N}x{K}, {len(rows)} sampled rows")
+        print(f"[full shape] {w.name} {name} {M}x{N}x{K}: {len(rows)} rows ok", flush=True)
         del xd, rd, yd
 
 
@@ -402,6 +403,7 @@ def sampled_check(w, lens, x, layers, y, picks, what, prefix=None):
         s_rms = logit_rms_of(x[b, :n], layers[0], w.n_heads, w.head_dim, w.ln_eps)
         assert_close(out, ref[0], w.dtype, f"{what}: sequence {int(b)} ({n} tokens)", stages=7 * L, logit_rms=s_rms,
                      attn_stages=L)
+        print(f"[sampled] {what}: sequence {int(b)} ({n} tokens) ok", flush=True)
 
 
 def zero_pads_nonzero_valid(y, lens):
