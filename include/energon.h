@@ -106,7 +106,10 @@ enum {
 
 const char* energon_strerror(int status);
 
-/* Bytes of workspace energon_layer_forward needs for up to max_tokens packed rows.
+/* Bytes of workspace energon_layer_forward needs for up to max_tokens packed rows: the six
+ * intermediates below plus, where the 16-bit contractions would cut tiles along K (see
+ * energon_linear_with_scratch), room for the pieces behind them.  A smaller workspace that still
+ * holds the intermediates of the actual T is accepted; the contractions then run without cutting.
  * Returns 0 if cfg is NULL/invalid or max_tokens < 0. */
 size_t energon_workspace_bytes(const EnergonLayerConfig* cfg, int64_t max_tokens);
 
@@ -183,6 +186,21 @@ int energon_layernorm(const void* x_dev, const void* gamma_dev, const void* beta
 int energon_linear(const void* x_dev, const void* w_dev, const void* bias_dev,
                    const void* residual_dev, void* y_dev, int64_t M, int32_t N, int32_t K,
                    int32_t epilogue, int32_t dtype, void* stream);
+
+/* energon_linear with room for intermediate sums.  For 16-bit problems of at least 192 tiles of
+ * 256 x 256 the contraction runs as one persistent workgroup per CU; the tiles beyond the last full
+ * round of workgroups would keep only part of the chip busy, so, given scratch, they are cut along
+ * K into equal shares, one per workgroup, the fp32 pieces meet in the scratch, and a second kernel
+ * adds them in a fixed order and applies the epilogue (same rounding points, a different but fixed
+ * order of the fp32 sums for the cut tiles; run-to-run identical).  energon_linear_scratch_bytes
+ * returns what a shape needs (0: it would not cut; then scratch may be NULL).  scratch_dev: 256-byte
+ * aligned, contents undefined afterwards.  energon_layer_forward does the same inside its
+ * workspace.  Other arguments and errors as energon_linear, plus CAPACITY (scratch too small). */
+size_t energon_linear_scratch_bytes(int64_t M, int32_t N, int32_t K, int32_t dtype);
+int energon_linear_with_scratch(const void* x_dev, const void* w_dev, const void* bias_dev,
+                                const void* residual_dev, void* y_dev, int64_t M, int32_t N, int32_t K,
+                                int32_t epilogue, int32_t dtype, void* scratch_dev, size_t scratch_bytes,
+                                void* stream);
 
 /* Causal attention of every sequence over its real length, on packed rows.
  *   qkv_dev [T, 3A]  (row t: Q | K | V, head h at columns h*d .. (h+1)*d-1 of each third)

@@ -71,6 +71,10 @@ def lib() -> C.CDLL:
         l.energon_layer_forward_profiled.argtypes = layer_args + [C.POINTER(C.c_float)]
         l.energon_layernorm.argtypes = [vp, vp, vp, vp, i64, i32, C.c_float, i32, vp]
         l.energon_linear.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
+        l.energon_linear_scratch_bytes.restype = sz
+        l.energon_linear_scratch_bytes.argtypes = [i64, i32, i32, i32]
+        l.energon_linear_with_scratch.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
+        l.energon_linear_with_scratch.restype = C.c_int
         l.energon_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         l.energon_rebuild_qkv.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         l.energon_attention_padded.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
@@ -234,6 +238,19 @@ def energon_linear(x, w, bias, residual, y, epilogue: int, stream=None) -> None:
     N = w.shape[0]
     _check(lib().energon_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K, int(epilogue),
                                 _dtype_code(x), _stream(stream)), "energon_linear")
+
+
+def energon_linear_scratch_bytes(M: int, N: int, K: int, dtype: int) -> int:
+    return int(lib().energon_linear_scratch_bytes(int(M), int(N), int(K), int(dtype)))
+
+
+def energon_linear_with_scratch(x, w, bias, residual, y, epilogue: int, scratch, stream=None) -> None:
+    M, K = x.shape
+    N = w.shape[0]
+    nbytes = 0 if scratch is None else int(scratch.numel() * scratch.element_size())
+    _check(lib().energon_linear_with_scratch(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K,
+                                             int(epilogue), _dtype_code(x), _ptr(scratch), nbytes, _stream(stream)),
+           "energon_linear_with_scratch")
 
 
 def energon_attention(qkv, out, cu_seqlens, B: int, max_len: int, n_heads: int, head_dim: int,

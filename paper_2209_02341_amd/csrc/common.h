@@ -151,6 +151,9 @@ bool gemm_emits_row_partials(int64_t M, int32_t N, int32_t K, bool res_aliases_y
 // split_scratch (optional, gemm_scratch_bytes(M, N, K) bytes): lets problems with few rows cut K over
 // several workgroups (partial sums in fp32, added in a fixed order by a second kernel).
 size_t gemm_split_scratch_bytes(int64_t M, int32_t N, int32_t K);
+// the part of the above that belongs to the persistent 256x256 kernel (0 if it does not take the shape
+// or would not cut tiles along K): room for two pieces of 256x256 fp32 accumulators per workgroup
+size_t gemm_sched_scratch_bytes(int64_t M, int32_t N, int32_t K);
 hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
                             int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr,
                             float* split_scratch = nullptr);

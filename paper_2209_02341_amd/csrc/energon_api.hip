@@ -58,6 +58,20 @@ WsLayout ws_layout(const EnergonLayerConfig* c, int64_t T) {
   return l;
 }
 
+// Room behind the six intermediates for the persistent 16-bit contraction kernel to leave the pieces
+// of tiles it cuts along K (the largest need of the layer's four contractions; 0 if none cuts).
+size_t layer_gemm_scratch_bytes(const EnergonLayerConfig* c, int64_t T) {
+  if (!is16(c->dtype) || T <= 0) return 0;
+  const int32_t H = c->hidden, A = c->n_heads * c->head_dim, F = c->ffn;
+  const int32_t shapes[4][2] = {{3 * A, H}, {H, A}, {F, H}, {H, F}};
+  size_t m = 0;
+  for (const auto& nk : shapes) {
+    const size_t b = gemm_sched_scratch_bytes(T, nk[0], nk[1]);
+    m = b > m ? b : m;
+  }
+  return m;
+}
+
 int linear_impl(const void* x, const void* w, const void* bias, const void* res, void* y, int64_t M, int32_t N,
                 int32_t K, int32_t epi, int32_t dt, hipStream_t s, const LnFold* fold = nullptr,
                 float* split_scratch = nullptr) {
@@ -128,10 +142,14 @@ int check_layer_args(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w
 // padws == nullptr: variable-length attention on the packed rows; otherwise the paper's path
 // (rebuild padding + transpose, padded attention, remove padding + transpose) through padws.
 int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y, int64_t T,
-               const int32_t* cu, int32_t B, int32_t max_len, void* ws, hipStream_t s, hipEvent_t* ev,
+               const int32_t* cu, int32_t B, int32_t max_len, void* ws, size_t ws_bytes, hipStream_t s, hipEvent_t* ev,
                void* padws = nullptr) {
   const WsLayout l = ws_layout(cfg, T);
   char* base = static_cast<char*>(ws);
+  // scratch of the contractions, if the caller's workspace has it (energon_workspace_bytes plans for it)
+  const size_t gs = layer_gemm_scratch_bytes(cfg, T);
+  float* const gscratch = gs > 0 && ws_bytes >= l.total + gs ? reinterpret_cast<float*>(base + l.total) : nullptr;
+  auto gemm_scratch = [&](int32_t N, int32_t K) { return gscratch && gemm_sched_scratch_bytes(T, N, K) > 0 ? gscratch : nullptr; };
   void* u = base + l.off[ENERGON_WS_U];
   void* qkv = base + l.off[ENERGON_WS_QKV];
   void* att = base + l.off[ENERGON_WS_ATTN];
@@ -145,7 +163,7 @@ int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, cons
   MARK(0);
   HIP_TRY(launch_layernorm(x, w->ln1_g, w->ln1_b, u, T, H, cfg->ln_eps, dt, s));
   MARK(1);
-  STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, T, 3 * A, H, ENERGON_EPI_BIAS, dt, s));
+  STEP(linear_impl(u, w->w_qkv, w->b_qkv, nullptr, qkv, T, 3 * A, H, ENERGON_EPI_BIAS, dt, s, nullptr, gemm_scratch(3 * A, H)));
   MARK(2);
   if (T > 0 && padws == nullptr) {
     STEP(attention_impl(qkv, att, cu, B, max_len, cfg->n_heads, cfg->head_dim, dt, s));
@@ -159,13 +177,13 @@ int layer_impl(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, cons
     HIP_TRY(launch_remove_padding_heads(pb + 3 * part, att, cu, B, max_len, cfg->n_heads, hb, s));
   }
   MARK(3);
-  STEP(linear_impl(att, w->w_o, w->b_o, x, y1, T, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+  STEP(linear_impl(att, w->w_o, w->b_o, x, y1, T, H, A, ENERGON_EPI_BIAS_RESIDUAL, dt, s, nullptr, gemm_scratch(H, A)));
   MARK(4);
   HIP_TRY(launch_layernorm(y1, w->ln2_g, w->ln2_b, wn, T, H, cfg->ln_eps, dt, s));
   MARK(5);
-  STEP(linear_impl(wn, w->w_fc1, w->b_fc1, nullptr, m, T, F, H, ENERGON_EPI_BIAS_GELU, dt, s));
+  STEP(linear_impl(wn, w->w_fc1, w->b_fc1, nullptr, m, T, F, H, ENERGON_EPI_BIAS_GELU, dt, s, nullptr, gemm_scratch(F, H)));
   MARK(6);
-  STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, T, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s));
+  STEP(linear_impl(m, w->w_fc2, w->b_fc2, y1, y, T, H, F, ENERGON_EPI_BIAS_RESIDUAL, dt, s, nullptr, gemm_scratch(H, F)));
   MARK(7);
 #undef MARK
 #undef STEP
@@ -231,7 +249,8 @@ int layer_folded_impl(const EnergonLayerConfig* cfg, const EnergonFoldedLayerWei
 
 // layer_impl with a HIP event between the stages; waits for the stream.
 int layer_timed(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x, void* y, int64_t T,
-                const int32_t* cu, int32_t B, int32_t max_len, void* ws, hipStream_t s, void* padws, float* stage_ms) {
+                const int32_t* cu, int32_t B, int32_t max_len, void* ws, size_t ws_bytes, hipStream_t s, void* padws,
+                float* stage_ms) {
   hipEvent_t ev[ENERGON_STAGE_COUNT + 1];
   int made = 0;
   for (; made <= ENERGON_STAGE_COUNT; ++made)
@@ -240,7 +259,7 @@ int layer_timed(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, con
     for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
     return ENERGON_ERR_HIP;
   }
-  int st = layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, s, ev, padws);
+  int st = layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, ws_bytes, s, ev, padws);
   if (st == ENERGON_OK && hipEventSynchronize(ev[ENERGON_STAGE_COUNT]) != hipSuccess) st = ENERGON_ERR_HIP;
   if (st == ENERGON_OK)
     for (int i = 0; i < ENERGON_STAGE_COUNT; ++i)
@@ -294,7 +313,7 @@ const char* energon_strerror(int status) {
 
 size_t energon_workspace_bytes(const EnergonLayerConfig* cfg, int64_t max_tokens) {
   if (check_cfg(cfg) != ENERGON_OK || max_tokens < 0) return 0;
-  const size_t t = ws_layout(cfg, max_tokens).total;
+  const size_t t = ws_layout(cfg, max_tokens).total + layer_gemm_scratch_bytes(cfg, max_tokens);
   return t ? t : 256;
 }
 
@@ -354,7 +373,7 @@ int energon_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeigh
                           size_t ws_bytes, void* stream) {
   const int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
   if (st != ENERGON_OK) return st;
-  return layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, static_cast<hipStream_t>(stream), nullptr);
+  return layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, ws_bytes, static_cast<hipStream_t>(stream), nullptr);
 }
 
 int energon_layer_forward_profiled(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x,
@@ -363,7 +382,7 @@ int energon_layer_forward_profiled(const EnergonLayerConfig* cfg, const EnergonL
   if (!stage_ms) return ENERGON_ERR_NULL;
   const int st = check_layer_args(cfg, w, x, y, T, cu, lengths, B, max_len, ws, ws_bytes);
   if (st != ENERGON_OK) return st;
-  return layer_timed(cfg, w, x, y, T, cu, B, max_len, ws, static_cast<hipStream_t>(stream), nullptr, stage_ms);
+  return layer_timed(cfg, w, x, y, T, cu, B, max_len, ws, ws_bytes, static_cast<hipStream_t>(stream), nullptr, stage_ms);
 }
 
 size_t energon_drce_workspace_bytes(const EnergonLayerConfig* cfg, int32_t B, int32_t S) {
@@ -422,8 +441,8 @@ int energon_layer_forward_drce(const EnergonLayerConfig* cfg, const EnergonLayer
   if ((int64_t)B * max_len >= ((int64_t)1 << 31) || (int64_t)B * cfg->n_heads >= (1 << 24)) return ENERGON_ERR_SHAPE;
   if (padws_bytes < energon_drce_workspace_bytes(cfg, B, max_len)) return ENERGON_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!stage_ms) return layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, s, nullptr, padws);
-  return layer_timed(cfg, w, x, y, T, cu, B, max_len, ws, s, padws, stage_ms);
+  if (!stage_ms) return layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, ws_bytes, s, nullptr, padws);
+  return layer_timed(cfg, w, x, y, T, cu, B, max_len, ws, ws_bytes, s, padws, stage_ms);
 }
 
 int energon_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t T, int32_t H, float eps,
@@ -449,6 +468,31 @@ int energon_linear(const void* x, const void* w, const void* bias, const void* r
   if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(y))
     return ENERGON_ERR_ALIGN;
   return linear_impl(x, w, bias, residual, y, M, N, K, epilogue, dtype, static_cast<hipStream_t>(stream));
+}
+
+size_t energon_linear_scratch_bytes(int64_t M, int32_t N, int32_t K, int32_t dtype) {
+  if (!is16(dtype) || M <= 0 || N <= 0 || K <= 0 || K % 64 != 0 || N % 8 != 0 || K >= kMaxReduction) return 0;
+  return round256(gemm_sched_scratch_bytes(M, N, K));
+}
+
+int energon_linear_with_scratch(const void* x, const void* w, const void* bias, const void* residual, void* y, int64_t M,
+                                int32_t N, int32_t K, int32_t epilogue, int32_t dtype, void* scratch,
+                                size_t scratch_bytes, void* stream) {
+  if (!x || !w || !y) return ENERGON_ERR_NULL;
+  if (!dtype_ok(dtype)) return ENERGON_ERR_UNSUPPORTED;
+  if (epilogue < ENERGON_EPI_BIAS || epilogue > ENERGON_EPI_BIAS_RESIDUAL) return ENERGON_ERR_UNSUPPORTED;
+  if (epilogue == ENERGON_EPI_BIAS_RESIDUAL && !residual) return ENERGON_ERR_NULL;
+  if (M < 0 || M >= ((int64_t)1 << 31) || N <= 0 || K <= 0) return ENERGON_ERR_SHAPE;
+  if (is16(dtype) ? (K % 64 != 0 || N % 8 != 0) : (K % 4 != 0 || N % 4 != 0)) return ENERGON_ERR_SHAPE;
+  if (K >= kMaxReduction) return ENERGON_ERR_UNSUPPORTED;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(bias) || !aligned16(residual) || !aligned16(y))
+    return ENERGON_ERR_ALIGN;
+  const size_t need = energon_linear_scratch_bytes(M, N, K, dtype);
+  if (need > 0 && !scratch) return ENERGON_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(scratch) & 255u) != 0) return ENERGON_ERR_ALIGN;
+  if (scratch_bytes < need) return ENERGON_ERR_CAPACITY;
+  return linear_impl(x, w, bias, residual, y, M, N, K, epilogue, dtype, static_cast<hipStream_t>(stream), nullptr,
+                     need > 0 ? static_cast<float*>(scratch) : nullptr);
 }
 
 int energon_attention(const void* qkv, void* out, const int32_t* cu, int64_t T, int32_t B, int32_t max_len,

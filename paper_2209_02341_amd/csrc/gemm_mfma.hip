@@ -141,13 +141,16 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
-template <typename E>
+// FOLD: the LayerNorm-folded epilogues and the row statistics of the residual epilogue are compiled
+// only into the instantiation that serves them; in the plain one their registers would push
+// accumulators out to scratch memory after every tile.
+template <typename E, bool FOLD>
 __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], const E* __restrict__ bias,
                                                      const E* res, E* y, int32_t N, int epi, int64_t mw,
                                                      int32_t nw, int lane, float* stage, const LnFold& lf) {
   const int lrow = lane & 15, lq = lane >> 4;
   const int rr = lane >> 4, c8 = (lane & 15) * 8;
-  const bool fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
+  const bool fold = FOLD && (epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU);
   float bv[8], cv[8];
 #pragma unroll
   for (int q = 0; q < 8; ++q) cv[q] = 0.f;
@@ -205,7 +208,7 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] += bv[q];
       }
-      if (epi == EPI_BIAS_GELU || epi == EPI_LNFOLD_GELU) {
+      if (epi == EPI_BIAS_GELU || (FOLD && epi == EPI_LNFOLD_GELU)) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] = gelu_erf(v[q]);
       }
@@ -217,7 +220,7 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
 #pragma unroll
       for (int q = 0; q < 8; ++q) o[q] = static_cast<E>(v[q]);
       __builtin_nontemporal_store(o, reinterpret_cast<vec8<E>*>(y + off));
-      if (lf.partial != nullptr) {  // the 16 lanes of this row hold one 128-column segment of it
+      if (FOLD && lf.partial != nullptr) {  // the 16 lanes of this row hold one 128-column segment of it
         float s1 = 0.f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) s1 += static_cast<float>(o[q]);
@@ -359,6 +362,88 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
 }
 
 // ---- hand-scheduled 256x256 kernel ----------------------------------------------------------
+// Work decomposition.  The kernel is persistent: 8 * wgs workgroups (one per CU: 128 KiB of LDS each),
+// workgroup id b running on XCD b % 8 as its workgroup j = b / 8.  Every XCD owns a fixed sequence
+// of tiles, and its workgroups walk it in rounds: workgroup j takes tiles j, j + wgs, j + 2 wgs, ...
+// so the tiles resident on an XCD at one time are wgs consecutive ones of its sequence, a compact
+// block that shares x and W slabs in that XCD's L2.
+//   raster 0: the tiles in bands of kGroupM row tiles, column by column inside a band, cut in 8 equal
+//             runs, one per XCD (resident block: 8 x 4 tiles);
+//   raster 1: XCD x owns row tiles [x R, (x + 1) R), R = tiles_m / 8, walked column by column (resident
+//             block R x wgs / R), all XCDs moving through the columns of W together, so that a W slab
+//             comes from HBM once and reaches the other seven L2s from the memory-side cache; the
+//             tiles_m % 8 leftover row tiles are dealt column-wise, 1/8 to each XCD, at the end.
+// With split = 1 the tiles of an XCD beyond its last full round (fewer than wgs) are not run as one
+// more, partly empty round: their rem * kt slabs are cut in wgs equal segments (even length), one per
+// workgroup.  A segment crosses at most a few tile borders; each stretch inside one tile is a
+// "piece".  A piece that is a whole tile is finished by its workgroup; any other piece leaves its fp32
+// accumulators in the caller's scratch (slot 2 * workgroup + (0 if the piece starts the segment, else
+// 1): a segment has at most one partial piece at its head and one at its tail), and a second kernel
+// adds the pieces of every cut tile in ascending K order and applies the epilogue: deterministic, no
+// atomics, no workgroup waits for another.  The Tail of a launch is thus one short, full round
+// instead of a long, partly empty one: that matters where a tile is long and rounds are few (the
+// tensor-parallel shard: 312 tiles of 192 slabs on 256 CUs).
+struct SchedPlan {
+  int32_t tiles_m, tiles_n, kt;   // kt: slabs of 64 along K per tile
+  int32_t wgs;                    // workgroups per XCD
+  int32_t raster;                 // 0 / 1, see above
+  int32_t split;                  // 1: remainder tiles cut along K
+};
+struct XcdShare { int32_t n_tiles, dp_rounds, rem, seg; };
+
+__host__ __device__ inline XcdShare xcd_share(const SchedPlan& p, int32_t x) {
+  XcdShare s;
+  if (p.raster == 1) {
+    const int32_t rows = p.tiles_m / kXcds, left = (p.tiles_m - kXcds * rows) * p.tiles_n;
+    const int32_t q = (left + kXcds - 1) / kXcds;
+    const int32_t mine = left - x * q;
+    s.n_tiles = rows * p.tiles_n + (mine < 0 ? 0 : (mine > q ? q : mine));
+  } else {
+    const int32_t total = p.tiles_m * p.tiles_n, per = (total + kXcds - 1) / kXcds;
+    const int32_t mine = total - x * per;
+    s.n_tiles = mine < 0 ? 0 : (mine > per ? per : mine);
+  }
+  if (p.split) {
+    s.dp_rounds = s.n_tiles / p.wgs;
+    s.rem = s.n_tiles - s.dp_rounds * p.wgs;
+    s.seg = (int32_t)(((int64_t)s.rem * p.kt + p.wgs - 1) / p.wgs);
+    s.seg += s.seg & 1;
+  } else {
+    s.dp_rounds = (s.n_tiles + p.wgs - 1) / p.wgs;   // the last one possibly not full
+    s.rem = 0;
+    s.seg = 0;
+  }
+  return s;
+}
+
+// Tile l of XCD x's sequence -> (row tile, column tile).
+__host__ __device__ inline void sched_tile(const SchedPlan& p, int32_t x, int32_t l, int32_t& tm, int32_t& tn) {
+  if (p.raster == 1) {
+    const int32_t rows = p.tiles_m / kXcds, main_n = rows * p.tiles_n;
+    if (l < main_n) {
+      tn = l / rows;
+      tm = x * rows + (l - tn * rows);
+    } else {
+      const int32_t left_rows = p.tiles_m - kXcds * rows;
+      const int32_t q = (left_rows * p.tiles_n + kXcds - 1) / kXcds;
+      const int32_t g = x * q + (l - main_n);
+      tn = g / left_rows;
+      tm = kXcds * rows + (g - tn * left_rows);
+    }
+  } else {
+    const int32_t total = p.tiles_m * p.tiles_n, per = (total + kXcds - 1) / kXcds;
+    const int32_t idx = x * per + l;
+    const int32_t band = idx / (kGroupM * p.tiles_n);
+    const int32_t first_m = band * kGroupM;
+    const int32_t band_m = p.tiles_m - first_m < kGroupM ? p.tiles_m - first_m : kGroupM;
+    const int32_t r = idx - band * kGroupM * p.tiles_n;
+    tn = r / band_m;
+    tm = first_m + (r - tn * band_m);
+  }
+}
+
+constexpr int kPartFloats = 256 * 256;   // one piece's accumulators
+
 // The slab loop is written as ordered inline-asm statements so that the issue order is exactly
 // the one below (the compiler otherwise re-serialises LDS reads and MFMAs, and it must not copy
 // or spill a register whose load is still in flight).  One wavefront per SIMD, 128x128 per
@@ -385,13 +470,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
       asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));               \
   } while (0)
 
-template <typename E, int BM, int BN, int WM, int WN>
+template <typename E, int BM, int BN, int WM, int WN, bool FOLD>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* __restrict__ x,
                                                                     const E* __restrict__ w,
                                                                     const E* __restrict__ bias,
                                                                     const E* res, E* y, int64_t M,
-                                                                    int32_t N, int32_t K, int epi, int32_t tiles_m,
-                                                                    int32_t tiles_n, LnFold lf) {
+                                                                    int32_t N, int32_t K, int epi, SchedPlan plan,
+                                                                    float* __restrict__ part, LnFold lf) {
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 16, TN = WTN / 16;
@@ -399,75 +484,111 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "row groups must divide evenly");
   static_assert((BM + BN) * 128 == 65536, "stage stride is assumed to be 64 KiB");
   static_assert(TM == 8 && TN == 8 && GA + GB == 16, "the hand schedule is written for 4 x (128x128)");
+  static_assert(BM * BN == kPartFloats, "a piece's accumulators");
   extern __shared__ uint4 smem[];  // [2][BM + BN][kChunks]
-
-  int64_t m0;
-  int32_t n0;
-  if (!tile_origin<BM, BN>(tiles_m, tiles_n, m0, n0)) return;
-  // Ragged edges: the last tile of a row / column of tiles is shifted back so that it ends at
-  // M / N (needs M >= BM, N >= BN).  It overlaps its neighbour; both compute bit-identical values
-  // for the shared elements, so no load is clamped and no store is predicated.
-  if (m0 > M - BM) m0 = M - BM;
-  if (n0 > N - BN) n0 = N - BN;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
-  // MFMA operand fragment of a 16-row tile for the step ks (32 along K = chunks 4 ks .. 4 ks + 3
-  // of the slab row): lane l holds row l % 16, chunk 4 ks + l / 16.  LDS byte address of that
-  // chunk for tile 0; tile t adds t * 2048 (16 rows), and swz depends on row % 16 only.
-  const int lrow = lane & 15, lq = lane >> 4;
-  uint32_t aaddr[2], baddr[2];
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const uint32_t chunk = (uint32_t)((ks * 4 + lq) ^ swz16(lrow)) * 16u;
-    aaddr[ks] = (uint32_t)(wm0 + lrow) * 128u + chunk;
-    baddr[ks] = (uint32_t)(BM + wn0 + lrow) * 128u + chunk;
-  }
+  // This workgroup's share: whole tiles first, then its segment of the XCD's split tiles.
+  const int32_t xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds;
+  const XcdShare share = xcd_share(plan, xcd);
+  const int32_t kt_all = plan.kt;
+  int32_t n_whole;   // whole tiles of this workgroup
+  if (plan.split) n_whole = share.dp_rounds;
+  else n_whole = share.n_tiles > wg ? (share.n_tiles - wg + plan.wgs - 1) / plan.wgs : 0;
+  const int32_t seg_first = wg * share.seg;
+  int32_t it = seg_first;
+  const int32_t seg_stop = min(seg_first + share.seg, share.rem * kt_all);
 
-  f32x4 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
-  // The compiler sees no MFMA (they are inside asm statements) and so adds no wait states between
-  // a register write and an MFMA that reads it: have the zeros written here, before the prologue.
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
-
-  const int KT = K / BK;
-
-  // Slab loads go straight from global memory to LDS (global_load_lds_dwordx4: no staging
-  // register, no LDS store instruction; LDS stores from registers would occupy the LDS pipeline
-  // longer than all the operand reads).  One instruction moves a row group: 8 rows x 128 bytes =
-  // 1 KiB of LDS in lane order, lane l landing in slot l % 8 of row l / 8 and fetching the chunk
-  // that the swizzle puts there.  The 64 row groups of a slab fall in four classes by the operand
-  // half that reads them -- AL / AH: x rows 0..63 / 64..127 of each wavefront row, BL / BH likewise
-  // for W -- and every wavefront moves 4 groups of each class, of its own parity (swz(row) depends
-  // on row % 16 = 8 * (group parity) + l / 8, so one per-lane offset serves all its groups).
-  const uint32_t voff = ((uint32_t)(lane >> 3) * (uint32_t)K + (uint32_t)(((lane & 7) ^ swz16((wave & 1) * 8 + (lane >> 3))) * 8)) * 2u;
-  const char* gsrc[4][4];  // [class AL, BH, BL, AH][j]: global address of the group's first row, slab 0
-  uint32_t ldst[4][4];     // its LDS byte offset in buffer 0
-#pragma unroll
-  for (int c = 0; c < 4; ++c)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bool is_a = (c == 0 || c == 3), high = (c == 1 || c == 3);
-      const int gl = 2 * ((wave >> 1) * 4 + j) + (wave & 1);           // 0..15 within the class
-      const int g = gl + (gl >= 8 ? 8 : 0) + (high ? 8 : 0);            // row group within the operand's 32
-      gsrc[c][j] = reinterpret_cast<const char*>((is_a ? x + (size_t)m0 * K : w + (size_t)n0 * K) + (size_t)(8 * g) * K);
-      ldst[c][j] = (uint32_t)((is_a ? 0 : BM * 128) + g * 1024);
+  for (int32_t done = 0;; ++done) {
+    // ---- next piece of work: tile l of the XCD's sequence, slabs [kb, kb + KT) of it ----
+    int32_t l, kb, KT;
+    float* piece_out = nullptr;   // non-null: the piece does not cover its tile
+    if (done < n_whole) {
+      l = done * plan.wgs + wg;
+      kb = 0;
+      KT = kt_all;
+    } else if (it < seg_stop) {
+      const int32_t t = it / kt_all;
+      l = share.dp_rounds * plan.wgs + t;
+      kb = it - t * kt_all;
+      KT = min(kt_all - kb, seg_stop - it);
+      if (KT != kt_all)
+        piece_out = part + (size_t)(2 * (xcd * plan.wgs + wg) + (it == seg_first ? 0 : 1)) * kPartFloats;
+      it += KT;
+    } else {
+      break;
     }
+    int32_t tm, tn;
+    sched_tile(plan, xcd, l, tm, tn);
+    int64_t m0 = (int64_t)tm * BM;
+    int32_t n0 = tn * BN;
+    // Ragged edges: the last tile of a row / column of tiles is shifted back so that it ends at
+    // M / N (needs M >= BM, N >= BN).  It overlaps its neighbour; both compute bit-identical values
+    // for the shared elements, so no load is clamped and no store is predicated.
+    if (m0 > M - BM) m0 = M - BM;
+    if (n0 > N - BN) n0 = N - BN;
+
+    // Per-lane addresses are derived afresh for every piece from an opaque copy of the lane id: kept
+    // alive across the epilogue instead, they would cost it registers it does not have.
+    int lane_i = lane;
+    asm volatile("" : "+v"(lane_i));
+    // MFMA operand fragment of a 16-row tile for the step ks (32 along K = chunks 4 ks .. 4 ks + 3
+    // of the slab row): lane l holds row l % 16, chunk 4 ks + l / 16.  LDS byte address of that
+    // chunk for tile 0; tile t adds t * 2048 (16 rows), and swz depends on row % 16 only.
+    const int lrow = lane_i & 15, lq = lane_i >> 4;
+    uint32_t aaddr[2], baddr[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const uint32_t chunk = (uint32_t)((ks * 4 + lq) ^ swz16(lrow)) * 16u;
+      aaddr[ks] = (uint32_t)(wm0 + lrow) * 128u + chunk;
+      baddr[ks] = (uint32_t)(BM + wn0 + lrow) * 128u + chunk;
+    }
+    // Slab loads go straight from global memory to LDS (global_load_lds_dwordx4: no staging
+    // register, no LDS store instruction; LDS stores from registers would occupy the LDS pipeline
+    // longer than all the operand reads).  One instruction moves a row group: 8 rows x 128 bytes =
+    // 1 KiB of LDS in lane order, lane l landing in slot l % 8 of row l / 8 and fetching the chunk
+    // that the swizzle puts there.  The 64 row groups of a slab fall in four classes by the operand
+    // half that reads them -- AL / AH: x rows 0..63 / 64..127 of each wavefront row, BL / BH likewise
+    // for W -- and every wavefront moves 4 groups of each class, of its own parity (swz(row) depends
+    // on row % 16 = 8 * (group parity) + l / 8, so one per-lane offset serves all its groups).
+    const uint32_t voff = ((uint32_t)(lane_i >> 3) * (uint32_t)K +
+                           (uint32_t)(((lane_i & 7) ^ swz16((wave & 1) * 8 + (lane_i >> 3))) * 8)) * 2u;
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+    // The compiler sees no MFMA (they are inside asm statements) and so adds no wait states between
+    // a register write and an MFMA that reads it: have the zeros written here, before the prologue.
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
+
+    const char* gsrc[4][4];  // [class AL, BH, BL, AH][j]: global address of the group's first row, slab kb
+    uint32_t ldst[4][4];     // its LDS byte offset in buffer 0
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool is_a = (c == 0 || c == 3), high = (c == 1 || c == 3);
+        const int gl = 2 * ((wave >> 1) * 4 + j) + (wave & 1);           // 0..15 within the class
+        const int g = gl + (gl >= 8 ? 8 : 0) + (high ? 8 : 0);            // row group within the operand's 32
+        gsrc[c][j] = reinterpret_cast<const char*>((is_a ? x + (size_t)m0 * K : w + (size_t)n0 * K) + (size_t)(8 * g) * K) +
+                     (size_t)kb * (BK * 2);
+        ldst[c][j] = (uint32_t)((is_a ? 0 : BM * 128) + g * 1024);
+      }
 #define ENERGON_DMA(c, j, kt_, buf)                                                                     \
   __builtin_amdgcn_global_load_lds((gptr_t)(gsrc[c][j] + (size_t)(kt_) * (BK * 2) + voff),              \
                                    (lptr_t)(reinterpret_cast<char*>(smem) + (buf) * 0x10000 + ldst[c][j]), 16, 0, 0)
 
-  vec8<E> fa[TM], fb[TN];  // the operand fragments: x-row tiles, W-row tiles
+    vec8<E> fa[TM], fb[TN];  // the operand fragments: x-row tiles, W-row tiles
 #define ENERGON_RA(t, ks) ENERGON_DS_READ(fa[t], aaddr[ks], (t) * 2048)
 #define ENERGON_RB(t, ks) ENERGON_DS_READ(fb[t], baddr[ks], (t) * 2048)
 #define ENERGON_MF(i, j) ENERGON_MFMA(acc[i][j], fa[i], fb[j])
@@ -497,31 +618,31 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   } while (0)
 #define ENERGON_READS_BACK asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
 
-  const int klast = KT - 1;
-  // Prologue: slab 0 into buffer 0 (waited for), slab 1 into buffer 1 (in flight), the fragments
-  // of the first quadrant in registers.  Load order within a slab is AL, BH, BL, AH throughout.
+    const int klast = KT - 1;
+    // Prologue: slab 0 into buffer 0 (waited for), slab 1 into buffer 1 (in flight), the fragments
+    // of the first quadrant in registers.  Load order within a slab is AL, BH, BL, AH throughout.
 #pragma unroll
-  for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ENERGON_DMA(c, j, 0, 0);
+      for (int j = 0; j < 4; ++j) ENERGON_DMA(c, j, 0, 0);
 #pragma unroll
-  for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ENERGON_DMA(c, j, (1 < klast ? 1 : klast), 1);
-  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  ENERGON_RA(0, 0); ENERGON_RA(1, 0); ENERGON_RA(2, 0); ENERGON_RA(3, 0);
-  ENERGON_RB(0, 0); ENERGON_RB(1, 0); ENERGON_RB(2, 0); ENERGON_RB(3, 0);
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      for (int j = 0; j < 4; ++j) ENERGON_DMA(c, j, (1 < klast ? 1 : klast), 1);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    ENERGON_RA(0, 0); ENERGON_RA(1, 0); ENERGON_RA(2, 0); ENERGON_RA(3, 0);
+    ENERGON_RB(0, 0); ENERGON_RB(1, 0); ENERGON_RB(2, 0); ENERGON_RB(3, 0);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
-  // Slab kt is consumed from buffer kt & 1 while slab kt+1 (other buffer) is landing.  Quadrants
-  // 2, 3, 4, 5 hold the last reads of the classes AL, BH, BL, AH of slab kt; the barrier that
-  // ends each of them frees that class's rows in the current buffer, and the loads of the same
-  // class of slab kt+2 follow in the next two quadrants.  Reads of slab kt+1 start in quadrant 6
-  // (AL), 7 (BL), then 0 (BH) and 1 (AH) of the next slab: the barriers ending quadrants 5, 6 and
-  // 0 are preceded by waits for exactly those classes (loads return in order; the count is the
-  // number of loads issued after the class's last).  A load thus has 8 to 10 quadrants, a good
-  // slab time, to arrive, and loads are issued in every quadrant but three.
+    // Slab kt is consumed from buffer kt & 1 while slab kt+1 (other buffer) is landing.  Quadrants
+    // 2, 3, 4, 5 hold the last reads of the classes AL, BH, BL, AH of slab kt; the barrier that
+    // ends each of them frees that class's rows in the current buffer, and the loads of the same
+    // class of slab kt+2 follow in the next two quadrants.  Reads of slab kt+1 start in quadrant 6
+    // (AL), 7 (BL), then 0 (BH) and 1 (AH) of the next slab: the barriers ending quadrants 5, 6 and
+    // 0 are preceded by waits for exactly those classes (loads return in order; the count is the
+    // number of loads issued after the class's last).  A load thus has 8 to 10 quadrants, a good
+    // slab time, to arrive, and loads are issued in every quadrant but three.
 #define ENERGON_SLAB(kt_, cur, nxt)                                                                     \
   {                                                                                                     \
     const int kl2 = (kt_) + 2 < KT ? (kt_) + 2 : klast;                                                 \
@@ -548,24 +669,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
                  ENERGON_DMA(3, 2, kl2, cur), ENERGON_DMA(3, 3, kl2, cur), ENERGON_NONE, ENERGON_NONE,   \
                  ENERGON_READS_BACK);                                                                   \
   }
-  for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0, checked by the launcher)
-    ENERGON_SLAB(kt, 0, 1)
-    ENERGON_SLAB(kt + 1, 1, 0)
-    // Last trip only: let the MFMA pipeline run empty before control leaves the loop.  Past this
-    // point the compiler moves accumulators between registers as it pleases, and it knows of no
-    // MFMA in flight (they are inside asm statements), so it would add none of the wait states
-    // that a read of a matrix-core result needs.
-    asm volatile("s_cmp_lt_i32 %0, %1\n\t"
-                 "s_cbranch_scc1 .Lenergon_more_%=\n\t"
-                 "s_nop 15\n\ts_nop 15\n\ts_nop 15\n"
-                 ".Lenergon_more_%=:"
-                 :
-                 : "s"(kt + 2), "s"(KT)
-                 : "scc", "memory");
-  }
+    for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0 and segments of even length)
+      ENERGON_SLAB(kt, 0, 1)
+      ENERGON_SLAB(kt + 1, 1, 0)
+      // Last trip only: let the MFMA pipeline run empty before control leaves the loop.  Past this
+      // point the compiler moves accumulators between registers as it pleases, and it knows of no
+      // MFMA in flight (they are inside asm statements), so it would add none of the wait states
+      // that a read of a matrix-core result needs.
+      asm volatile("s_cmp_lt_i32 %0, %1\n\t"
+                   "s_cbranch_scc1 .Lenergon_more_%=\n\t"
+                   "s_nop 15\n\ts_nop 15\n\ts_nop 15\n"
+                   ".Lenergon_more_%=:"
+                   :
+                   : "s"(kt + 2), "s"(KT)
+                   : "scc", "memory");
+    }
 #undef ENERGON_SLAB
-  // Outstanding loads (the clamped refetches of the last slabs) still write to LDS.
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // Outstanding loads (the clamped refetches of the last slabs) still write to LDS.
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #undef ENERGON_DMA
 #undef ENERGON_QUAD
 #undef ENERGON_SYNC
@@ -575,12 +696,69 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
 #undef ENERGON_RB
 #undef ENERGON_MF
 
-  // The epilogue's per-lane addresses must not be computed (and kept live) above the slab loop,
-  // where every VGPR is spoken for: route the lane id through an ordered asm statement.
-  int lane_e = lane;
-  asm volatile("" : "+v"(lane_e));
-  store_tile_coalesced(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
-                       reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf);
+    // The epilogue's per-lane addresses must not be computed (and kept live) above the slab loop,
+    // where every VGPR is spoken for: route the lane id through an ordered asm statement.
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    if (piece_out != nullptr) {
+      // a piece of a cut tile: the accumulators as they are, 16 bytes per lane and store (1 KiB
+      // contiguous per instruction), in the order [wavefront][i][j][lane].  Stored straight from the
+      // accumulator registers: left to the compiler, all 256 are first copied to VGPRs at once, which
+      // costs the whole kernel spills to scratch memory after every tile.
+      char* dst = reinterpret_cast<char*>(piece_out) + ((size_t)wave * (TM * TN * 64) + lane_e) * sizeof(f32x4);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(dst + (size_t)(i * TN + j) * 1024), "a"(acc[i][j]) : "memory");
+    } else {
+      store_tile_coalesced<E, FOLD>(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
+                                    reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf);
+    }
+    // the slab buffers (or the staging rows over them) are reused by the next piece's first loads
+    __syncthreads();
+  }
+}
+
+// Second kernel of a split launch: workgroup (x, t) = blockIdx.x % 8, blockIdx.x / 8 finishes cut
+// tile t of XCD x.  It adds the tile's pieces in ascending K order into the accumulator layout of
+// the kernel above (same thread <-> element map, so a piece is read back exactly as it was
+// written) and runs the same epilogue.  A tile that one piece covered was finished there.
+template <typename E, bool FOLD>
+__global__ __launch_bounds__(256) void gemm_mfma_fixup_kernel(const float* __restrict__ part,
+                                                             const E* __restrict__ bias, const E* res, E* y,
+                                                             int64_t M, int32_t N, int epi, SchedPlan plan, LnFold lf) {
+  extern __shared__ uint4 smem[];
+  const int32_t xcd = blockIdx.x % kXcds, t = blockIdx.x / kXcds;
+  const XcdShare share = xcd_share(plan, xcd);
+  if (t >= share.rem) return;
+  const int32_t it0 = t * plan.kt, it1 = it0 + plan.kt;
+  const int32_t r0 = it0 / share.seg, r1 = (it1 - 1) / share.seg;
+  if (r0 == r1) return;   // one piece = the whole tile
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  f32x4 acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int32_t r = r0; r <= r1; ++r) {
+    const int32_t first = r * share.seg;
+    const int32_t slot = 2 * (xcd * plan.wgs + r) + (first >= it0 ? 0 : 1);   // the piece starts its segment, or not
+    const f32x4* src = reinterpret_cast<const f32x4*>(part + (size_t)slot * kPartFloats) + (size_t)wave * (64 * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] += src[(i * 8 + j) * 64];
+  }
+  int32_t tm, tn;
+  sched_tile(plan, xcd, share.dp_rounds * plan.wgs + t, tm, tn);
+  int64_t m0 = (int64_t)tm * 256;
+  int32_t n0 = tn * 256;
+  if (m0 > M - 256) m0 = M - 256;
+  if (n0 > N - 256) n0 = N - 256;
+  store_tile_coalesced<E, FOLD>(acc, bias, res, y, N, epi, m0 + (wave / 2) * 128, n0 + (wave % 2) * 128, lane,
+                                reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf);
 }
 
 template <typename E, typename Kern>
@@ -615,8 +793,60 @@ bool gemm_emits_row_partials(int64_t M, int32_t N, int32_t K, bool res_aliases_y
   return takes_sched_kernel(M, N, K, res_aliases_y) && N % 256 == 0;
 }
 
-// Tile size and number of K parts for the split path: enough workgroups (>= 512 where K allows), every
-// part at least 16 slabs long.
+// Workgroups per XCD for the persistent 256x256 kernel: one per CU (MI355X: 256 CUs in 8 XCDs).
+static int32_t sched_wgs_per_xcd() {
+  static int32_t cached[32] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 32;
+  const bool tracked = dev >= 0 && dev < 32;
+  if (tracked && cached[dev] > 0) return cached[dev];
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kXcds) cus = 256;
+  const int32_t v = cus / kXcds;
+  if (tracked) cached[dev] = v;
+  return v;
+}
+
+// Decomposition of a launch of the 256x256 kernel.  Raster: a row band per XCD once every XCD gets
+// at least two row tiles (all XCDs then stream the same W columns at the same time), band order
+// otherwise.  Split: cut the remainder tiles along K if that, with its second kernel, is expected to
+// beat one more partly filled round by 3 % or more.  Times in slab units of a busy chip (a 256x256x64
+// slab step takes about 1.55 us under the sustained power limit); the second kernel reads every piece
+// once, at about 3 TB/s including its own stores, after a launch gap.
+static SchedPlan sched_plan(int64_t M, int32_t N, int32_t K, bool can_split, int32_t wgs) {
+  SchedPlan p;
+  p.tiles_m = (int32_t)((M + 255) / 256);
+  p.tiles_n = (N + 255) / 256;
+  p.kt = K / BK;
+  p.wgs = wgs;
+  p.raster = p.tiles_m >= 2 * kXcds ? 1 : 0;
+  p.split = 0;
+  if (!can_split) return p;
+  SchedPlan q = p;
+  q.split = 1;
+  double whole = 0, cut = 0, pieces = 0;
+  for (int32_t x = 0; x < kXcds; ++x) {   // the slowest XCD sets the time
+    const XcdShare a = xcd_share(p, x), b = xcd_share(q, x);
+    const double ta = (double)a.dp_rounds * p.kt, tb = (double)b.dp_rounds * p.kt + b.seg;
+    whole = ta > whole ? ta : whole;
+    cut = tb > cut ? tb : cut;
+    if (b.rem > 0) pieces += b.rem + wgs;   // every segment border and every tile border starts a piece
+  }
+  if (pieces == 0) return p;
+  const double slab_us = 1.55, fix_us = 8.0 + pieces * (kPartFloats * 4.0) / 3.0e6;
+  if (cut * slab_us + fix_us < 0.97 * whole * slab_us) p.split = 1;
+  return p;
+}
+
+size_t gemm_sched_scratch_bytes(int64_t M, int32_t N, int32_t K) {
+  if (!takes_sched_kernel(M, N, K, false)) return 0;
+  const int32_t wgs = sched_wgs_per_xcd();
+  if (!sched_plan(M, N, K, true, wgs).split) return 0;
+  return (size_t)2 * kXcds * wgs * kPartFloats * sizeof(float);
+}
+
+// Tile size and number of K parts for the split path of the compiler-scheduled kernel: enough
+// workgroups (>= 512 where K allows), every part at least 16 slabs long.
 void gemm_split_plan(int64_t M, int32_t N, int32_t K, int32_t* tile, int32_t* ks) {
   const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
   const int32_t t = tiles128 < 128 ? 64 : 128;
@@ -629,16 +859,39 @@ void gemm_split_plan(int64_t M, int32_t N, int32_t K, int32_t* tile, int32_t* ks
 }
 
 size_t gemm_split_scratch_bytes(int64_t M, int32_t N, int32_t K) {
+  if (takes_sched_kernel(M, N, K, false)) return gemm_sched_scratch_bytes(M, N, K);
   int32_t tile, ks;
   gemm_split_plan(M, N, K, &tile, &ks);
   return ks > 1 ? (size_t)ks * (size_t)M * N * sizeof(float) : 0;
+}
+
+template <typename E, bool FOLD>
+static hipError_t launch_sched(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
+                               int32_t K, int epi, const LnFold& lf, hipStream_t s, float* scratch) {
+  constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
+  constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
+  constexpr size_t lds = slabs > epi_stage ? slabs : epi_stage;
+  static LdsAttrOnce attr_main, attr_fix;   // per element type and FOLD
+  auto kern = gemm_mfma_sched_kernel<E, 256, 256, 2, 2, FOLD>;
+  auto fix = gemm_mfma_fixup_kernel<E, FOLD>;
+  hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, attr_main);
+  if (e != hipSuccess) return e;
+  const int32_t wgs = sched_wgs_per_xcd();
+  const SchedPlan plan = sched_plan(M, N, K, scratch != nullptr, wgs);
+  kern<<<dim3((unsigned)(kXcds * wgs)), dim3(256), lds, s>>>(x, w, bias, res, y, M, N, K, epi, plan, scratch, lf);
+  e = hipGetLastError();
+  if (e != hipSuccess || !plan.split) return e;
+  e = ensure_dynamic_lds(reinterpret_cast<const void*>(fix), epi_stage, attr_fix);
+  if (e != hipSuccess) return e;
+  fix<<<dim3((unsigned)(kXcds * wgs)), dim3(256), epi_stage, s>>>(scratch, bias, res, y, M, N, epi, plan, lf);
+  return hipGetLastError();
 }
 
 template <typename E>
 static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
                                    int32_t K, int epi, hipStream_t s, const LnFold* fold, float* split_scratch) {
   if (M <= 0) return hipSuccess;
-  static LdsAttrOnce attr_big, attr_small, attr_small_fold;  // per element type
+  static LdsAttrOnce attr_small, attr_small_fold;  // per element type
   const LnFold lf = fold != nullptr ? *fold : LnFold{};
   const bool wants_fold = epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU;
   if (wants_fold && (lf.stats == nullptr || lf.colsum == nullptr || lf.bias == nullptr)) return hipErrorInvalidValue;
@@ -646,15 +899,13 @@ static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const 
     return hipErrorInvalidValue;
   if (lf.partial == nullptr && gemm_skinny_takes(M, N, K, epi))
     return launch_gemm_skinny<E>(x, w, bias, res, y, M, N, K, epi, s, split_scratch);
-  if (takes_sched_kernel(M, N, K, res == y)) {
-    constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
-    constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
-    return launch_tiles<E>(gemm_mfma_sched_kernel<E, 256, 256, 2, 2>, attr_big, 256, 256, 256,
-                           slabs > epi_stage ? slabs : epi_stage, x, w, bias, res, y, M, N, K, epi, lf, s);
-  }
+  if (takes_sched_kernel(M, N, K, res == y))
+    return wants_fold || lf.partial != nullptr ? launch_sched<E, true>(x, w, bias, res, y, M, N, K, epi, lf, s, split_scratch)
+                                               : launch_sched<E, false>(x, w, bias, res, y, M, N, K, epi, lf, s, split_scratch);
   // A batch of a generation step too large for the few-row kernel, with scratch from the caller: K cut
-  // over workgroups until there are enough of them, the parts added by a second kernel.
-  if (split_scratch != nullptr && !wants_fold && lf.partial == nullptr) {
+  // over workgroups until there are enough of them, the parts added by a second kernel.  (Not where only
+  // the aliased residual kept the shape from the 256x256 kernel: the scratch was sized for that one.)
+  if (split_scratch != nullptr && !wants_fold && lf.partial == nullptr && !takes_sched_kernel(M, N, K, false)) {
     int32_t tile, ks;
     gemm_split_plan(M, N, K, &tile, &ks);
     if (ks > 1) {
