@@ -373,23 +373,32 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
 //             block R x wgs / R), all XCDs moving through the columns of W together, so that a W slab
 //             comes from HBM once and reaches the other seven L2s from the memory-side cache; the
 //             tiles_m % 8 leftover row tiles are dealt column-wise, 1/8 to each XCD, at the end.
-// With split = 1 the tiles of an XCD beyond its last full round (fewer than wgs) are not run as one
-// more, partly empty round: their rem * kt slabs are cut in wgs equal segments (even length), one per
-// workgroup.  A segment crosses at most a few tile borders; each stretch inside one tile is a
-// "piece".  A piece that is a whole tile is finished by its workgroup; any other piece leaves its fp32
-// accumulators in the caller's scratch (slot 2 * workgroup + (0 if the piece starts the segment, else
-// 1): a segment has at most one partial piece at its head and one at its tail), and a second kernel
-// adds the pieces of every cut tile in ascending K order and applies the epilogue: deterministic, no
-// atomics, no workgroup waits for another.  The Tail of a launch is thus one short, full round
-// instead of a long, partly empty one: that matters where a tile is long and rounds are few (the
+// With pieces = P > 1 the tiles of an XCD beyond its last full round (fewer than wgs) are not run as
+// one more, partly empty round: each is cut along K into P chunks of the same even length (the last
+// one shorter), chunk borders at the same slabs for every tile, and the rem * P pieces are dealt to
+// the XCD's workgroups chunk by chunk (piece q = chunk * rem + tile, workgroup j takes q = j, j + wgs,
+// ...).  Workgroups of a round thus walk the same slabs at the same time and keep sharing x and W
+// slabs in the L2, as whole tiles do.  (Cutting the remainder's slabs into wgs equal contiguous
+// shares, the textbook stream-K cut, balances better but starts every workgroup at a different K
+// offset: measured on the tensor-parallel shard's QKV shape it took the L2 hit rate down far enough
+// to make the launch 1.7 times slower than with whole tiles.)  A piece leaves its fp32 accumulators
+// in the caller's scratch, slot tile * P + chunk of its XCD; a second kernel adds the P pieces of
+// every cut tile in ascending K order and applies the epilogue: deterministic, no atomics, no
+// workgroup waits for another.  The tail of a launch is then a short, well filled round instead of
+// a long, partly empty one: that matters where a tile is long and rounds are few (the
 // tensor-parallel shard: 312 tiles of 192 slabs on 256 CUs).
 struct SchedPlan {
   int32_t tiles_m, tiles_n, kt;   // kt: slabs of 64 along K per tile
   int32_t wgs;                    // workgroups per XCD
   int32_t raster;                 // 0 / 1, see above
-  int32_t split;                  // 1: remainder tiles cut along K
+  int32_t pieces;                 // P: 1 = remainder tiles run whole
 };
-struct XcdShare { int32_t n_tiles, dp_rounds, rem, seg; };
+struct XcdShare { int32_t n_tiles, dp_rounds, rem, chunk; };   // chunk: slabs per piece
+
+__host__ __device__ inline int32_t sched_chunk(int32_t kt, int32_t pieces) {
+  int32_t c = (kt + pieces - 1) / pieces;
+  return c + (c & 1);
+}
 
 __host__ __device__ inline XcdShare xcd_share(const SchedPlan& p, int32_t x) {
   XcdShare s;
@@ -403,15 +412,14 @@ __host__ __device__ inline XcdShare xcd_share(const SchedPlan& p, int32_t x) {
     const int32_t mine = total - x * per;
     s.n_tiles = mine < 0 ? 0 : (mine > per ? per : mine);
   }
-  if (p.split) {
+  if (p.pieces > 1) {
     s.dp_rounds = s.n_tiles / p.wgs;
     s.rem = s.n_tiles - s.dp_rounds * p.wgs;
-    s.seg = (int32_t)(((int64_t)s.rem * p.kt + p.wgs - 1) / p.wgs);
-    s.seg += s.seg & 1;
+    s.chunk = sched_chunk(p.kt, p.pieces);
   } else {
     s.dp_rounds = (s.n_tiles + p.wgs - 1) / p.wgs;   // the last one possibly not full
     s.rem = 0;
-    s.seg = 0;
+    s.chunk = p.kt;
   }
   return s;
 }
@@ -491,16 +499,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
-  // This workgroup's share: whole tiles first, then its segment of the XCD's split tiles.
+  // This workgroup's share: whole tiles first, then its pieces of the XCD's cut tiles.
   const int32_t xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds;
   const XcdShare share = xcd_share(plan, xcd);
   const int32_t kt_all = plan.kt;
   int32_t n_whole;   // whole tiles of this workgroup
-  if (plan.split) n_whole = share.dp_rounds;
+  if (plan.pieces > 1) n_whole = share.dp_rounds;
   else n_whole = share.n_tiles > wg ? (share.n_tiles - wg + plan.wgs - 1) / plan.wgs : 0;
-  const int32_t seg_first = wg * share.seg;
-  int32_t it = seg_first;
-  const int32_t seg_stop = min(seg_first + share.seg, share.rem * kt_all);
+  const int32_t n_chunks = (kt_all + share.chunk - 1) / share.chunk;   // <= plan.pieces
+  const int32_t q_stop = share.rem * n_chunks;
+  int32_t q = wg;   // next piece
 
   for (int32_t done = 0;; ++done) {
     // ---- next piece of work: tile l of the XCD's sequence, slabs [kb, kb + KT) of it ----
@@ -510,14 +518,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
       l = done * plan.wgs + wg;
       kb = 0;
       KT = kt_all;
-    } else if (it < seg_stop) {
-      const int32_t t = it / kt_all;
+    } else if (q < q_stop) {
+      const int32_t c = q / share.rem, t = q - c * share.rem;
       l = share.dp_rounds * plan.wgs + t;
-      kb = it - t * kt_all;
-      KT = min(kt_all - kb, seg_stop - it);
-      if (KT != kt_all)
-        piece_out = part + (size_t)(2 * (xcd * plan.wgs + wg) + (it == seg_first ? 0 : 1)) * kPartFloats;
-      it += KT;
+      kb = c * share.chunk;
+      KT = min(share.chunk, kt_all - kb);
+      piece_out = part + ((size_t)xcd * (2 * plan.wgs) + (size_t)(t * plan.pieces + c)) * kPartFloats;
+      q += plan.wgs;
     } else {
       break;
     }
@@ -669,7 +676,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
                  ENERGON_DMA(3, 2, kl2, cur), ENERGON_DMA(3, 3, kl2, cur), ENERGON_NONE, ENERGON_NONE,   \
                  ENERGON_READS_BACK);                                                                   \
   }
-    for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0 and segments of even length)
+    for (int kt = 0; kt < KT; kt += 2) {  // KT is even (K % 128 == 0 and chunks of even length)
       ENERGON_SLAB(kt, 0, 1)
       ENERGON_SLAB(kt + 1, 1, 0)
       // Last trip only: let the MFMA pipeline run empty before control leaves the loop.  Past this
@@ -720,45 +727,76 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   }
 }
 
-// Second kernel of a split launch: workgroup (x, t) = blockIdx.x % 8, blockIdx.x / 8 finishes cut
-// tile t of XCD x.  It adds the tile's pieces in ascending K order into the accumulator layout of
-// the kernel above (same thread <-> element map, so a piece is read back exactly as it was
-// written) and runs the same epilogue.  A tile that one piece covered was finished there.
-template <typename E, bool FOLD>
+// Second kernel of a launch that cut tiles.  A workgroup finishes a strip of 16 rows x 128 columns
+// of one cut tile (the 8 accumulator tiles j = 0..7 of row i of one wavefront's quadrant; 32 strips per
+// tile): every thread adds, in ascending K order, the P pieces of two 16-byte accumulator vectors
+// (all loads issued before the first add), the strip is turned through LDS, and each thread then
+// owns 8 consecutive columns of a row: bias, GeLU / residual in fp32, one rounding, one 16-byte
+// store.  blockIdx.x % 8 is the XCD that wrote the pieces.
+constexpr int kFixStrips = 32;
+template <typename E>
 __global__ __launch_bounds__(256) void gemm_mfma_fixup_kernel(const float* __restrict__ part,
                                                              const E* __restrict__ bias, const E* res, E* y,
-                                                             int64_t M, int32_t N, int epi, SchedPlan plan, LnFold lf) {
-  extern __shared__ uint4 smem[];
-  const int32_t xcd = blockIdx.x % kXcds, t = blockIdx.x / kXcds;
+                                                             int64_t M, int32_t N, int epi, SchedPlan plan) {
+  __shared__ float stage[16 * kEpiLd];
+  const int32_t xcd = blockIdx.x % kXcds, rest = blockIdx.x / kXcds;
+  const int32_t t = rest / kFixStrips, strip = rest % kFixStrips;
   const XcdShare share = xcd_share(plan, xcd);
   if (t >= share.rem) return;
-  const int32_t it0 = t * plan.kt, it1 = it0 + plan.kt;
-  const int32_t r0 = it0 / share.seg, r1 = (it1 - 1) / share.seg;
-  if (r0 == r1) return;   // one piece = the whole tile
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  f32x4 acc[8][8];
+  const int32_t n_chunks = (plan.kt + share.chunk - 1) / share.chunk;
+  const int quad = strip >> 3, i = strip & 7;
+  const int tid = threadIdx.x, lane = tid & 63, jw = tid >> 6;   // this thread: accumulator tiles j = 2 jw, 2 jw + 1
+  const f32x4* src = reinterpret_cast<const f32x4*>(part + ((size_t)xcd * (2 * plan.wgs) + (size_t)t * plan.pieces) * kPartFloats) +
+                     ((size_t)quad * 64 + i * 8 + 2 * jw) * 64 + lane;
+  f32x4 sum[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+  for (int32_t c0 = 0; c0 < n_chunks; c0 += 4) {   // four pieces' loads in flight at a time
+    f32x4 v[4][2];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int32_t r = r0; r <= r1; ++r) {
-    const int32_t first = r * share.seg;
-    const int32_t slot = 2 * (xcd * plan.wgs + r) + (first >= it0 ? 0 : 1);   // the piece starts its segment, or not
-    const f32x4* src = reinterpret_cast<const f32x4*>(part + (size_t)slot * kPartFloats) + (size_t)wave * (64 * 64) + lane;
+      for (int u = 0; u < 2; ++u)
+        v[c][u] = c0 + c < n_chunks ? src[(size_t)(c0 + c) * (kPartFloats / 4) + u * 64] : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[i][j] += src[(i * 8 + j) * 64];
+      for (int u = 0; u < 2; ++u) sum[u] += v[c][u];
   }
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) stage[((lane >> 4) * 4 + e) * kEpiLd + (2 * jw + u) * 16 + (lane & 15)] = sum[u][e];
+  __syncthreads();
   int32_t tm, tn;
   sched_tile(plan, xcd, share.dp_rounds * plan.wgs + t, tm, tn);
   int64_t m0 = (int64_t)tm * 256;
   int32_t n0 = tn * 256;
   if (m0 > M - 256) m0 = M - 256;
   if (n0 > N - 256) n0 = N - 256;
-  store_tile_coalesced<E, FOLD>(acc, bias, res, y, N, epi, m0 + (wave / 2) * 128, n0 + (wave % 2) * 128, lane,
-                                reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf);
+  const int r = tid >> 4, c8 = (tid & 15) * 8;
+  const int64_t m = m0 + (quad >> 1) * 128 + i * 16 + r;
+  const int32_t n = n0 + (quad & 1) * 128 + c8;
+  const float4 lo = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8]);
+  const float4 hi = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8 + 4]);
+  float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  if (bias != nullptr) {
+    const vec8<E> b8 = *reinterpret_cast<const vec8<E>*>(bias + n);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] += static_cast<float>(b8[q]);
+  }
+  if (epi == EPI_BIAS_GELU) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = gelu_erf(v[q]);
+  }
+  const size_t off = (size_t)m * N + n;
+  if (epi == EPI_BIAS_RESIDUAL) {
+    const vec8<E> r8 = *reinterpret_cast<const vec8<E>*>(res + off);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] += static_cast<float>(r8[q]);
+  }
+  vec8<E> o;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) o[q] = static_cast<E>(v[q]);
+  *reinterpret_cast<vec8<E>*>(y + off) = o;
 }
 
 template <typename E, typename Kern>
@@ -809,10 +847,11 @@ static int32_t sched_wgs_per_xcd() {
 
 // Decomposition of a launch of the 256x256 kernel.  Raster: a row band per XCD once every XCD gets
 // at least two row tiles (all XCDs then stream the same W columns at the same time), band order
-// otherwise.  Split: cut the remainder tiles along K if that, with its second kernel, is expected to
-// beat one more partly filled round by 3 % or more.  Times in slab units of a busy chip (a 256x256x64
-// slab step takes about 1.55 us under the sustained power limit); the second kernel reads every piece
-// once, at about 3 TB/s including its own stores, after a launch gap.
+// otherwise.  Pieces: the P in 1..8 (P rem <= 2 wgs: the scratch has 2 wgs slots per XCD) with the
+// least expected time, in slab units of a busy chip (a 256x256x64 slab step takes about 1.55 us
+// under the sustained power limit): the remainder's rounds of pieces, plus, for P > 1, each piece's
+// start-up and accumulator store and the second kernel (it reads every piece once at about 3 TB/s
+// including its own stores, after a launch gap).  P > 1 has to win by 3 % of the launch.
 static SchedPlan sched_plan(int64_t M, int32_t N, int32_t K, bool can_split, int32_t wgs) {
   SchedPlan p;
   p.tiles_m = (int32_t)((M + 255) / 256);
@@ -820,28 +859,58 @@ static SchedPlan sched_plan(int64_t M, int32_t N, int32_t K, bool can_split, int
   p.kt = K / BK;
   p.wgs = wgs;
   p.raster = p.tiles_m >= 2 * kXcds ? 1 : 0;
-  p.split = 0;
+  p.pieces = 1;
   if (!can_split) return p;
-  SchedPlan q = p;
-  q.split = 1;
-  double whole = 0, cut = 0, pieces = 0;
-  for (int32_t x = 0; x < kXcds; ++x) {   // the slowest XCD sets the time
-    const XcdShare a = xcd_share(p, x), b = xcd_share(q, x);
-    const double ta = (double)a.dp_rounds * p.kt, tb = (double)b.dp_rounds * p.kt + b.seg;
-    whole = ta > whole ? ta : whole;
-    cut = tb > cut ? tb : cut;
-    if (b.rem > 0) pieces += b.rem + wgs;   // every segment border and every tile border starts a piece
+  // per XCD: full rounds and remainder tiles (they differ by a tile between XCDs)
+  int32_t full[kXcds], rem[kXcds], rem_max = 0;
+  for (int32_t x = 0; x < kXcds; ++x) {
+    const int32_t n = xcd_share(p, x).n_tiles;
+    full[x] = n / wgs;
+    rem[x] = n - full[x] * wgs;
+    rem_max = rem[x] > rem_max ? rem[x] : rem_max;
   }
-  if (pieces == 0) return p;
-  const double slab_us = 1.55, fix_us = 8.0 + pieces * (kPartFloats * 4.0) / 3.0e6;
-  if (cut * slab_us + fix_us < 0.97 * whole * slab_us) p.split = 1;
+  if (rem_max == 0) return p;
+  const double slab_us = 1.55, piece_us = 6.0;
+  auto launch_time = [&](int32_t P, int32_t chunk) {   // the slowest XCD sets the time
+    double worst = 0;
+    for (int32_t x = 0; x < kXcds; ++x) {
+      const int32_t rounds = (rem[x] * P + wgs - 1) / wgs;
+      const double t = (double)full[x] * p.kt * slab_us + rounds * (chunk * slab_us + (P > 1 ? piece_us : 0.0));
+      worst = t > worst ? t : worst;
+    }
+    return worst;
+  };
+  const double whole = launch_time(1, p.kt);
+  double best = whole;
+  for (int32_t P = 2; P <= 8 && P * rem_max <= 2 * wgs; ++P) {
+    const int32_t chunk = sched_chunk(p.kt, P), n_chunks = (p.kt + chunk - 1) / chunk;
+    if (n_chunks != P || chunk < 8) continue;
+    int32_t cut_tiles = 0;
+    for (int32_t x = 0; x < kXcds; ++x) cut_tiles += rem[x];
+    const double fix_us = 8.0 + (double)cut_tiles * P * (kPartFloats * 4.0) / 3.0e6;
+    const double t = launch_time(P, chunk) + fix_us;
+    if (t < best && whole - t > 0.03 * whole) {
+      best = t;
+      p.pieces = P;
+    }
+  }
   return p;
+}
+
+// the most cut tiles any XCD has under a plan
+static int32_t sched_max_rem(const SchedPlan& p) {
+  int32_t m = 0;
+  for (int32_t x = 0; x < kXcds; ++x) {
+    const int32_t r = xcd_share(p, x).rem;
+    m = r > m ? r : m;
+  }
+  return m;
 }
 
 size_t gemm_sched_scratch_bytes(int64_t M, int32_t N, int32_t K) {
   if (!takes_sched_kernel(M, N, K, false)) return 0;
   const int32_t wgs = sched_wgs_per_xcd();
-  if (!sched_plan(M, N, K, true, wgs).split) return 0;
+  if (sched_plan(M, N, K, true, wgs).pieces == 1) return 0;
   return (size_t)2 * kXcds * wgs * kPartFloats * sizeof(float);
 }
 
@@ -871,19 +940,19 @@ static hipError_t launch_sched(const E* x, const E* w, const E* bias, const E* r
   constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
   constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
   constexpr size_t lds = slabs > epi_stage ? slabs : epi_stage;
-  static LdsAttrOnce attr_main, attr_fix;   // per element type and FOLD
+  static LdsAttrOnce attr_main;   // per element type and FOLD
   auto kern = gemm_mfma_sched_kernel<E, 256, 256, 2, 2, FOLD>;
-  auto fix = gemm_mfma_fixup_kernel<E, FOLD>;
   hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, attr_main);
   if (e != hipSuccess) return e;
   const int32_t wgs = sched_wgs_per_xcd();
-  const SchedPlan plan = sched_plan(M, N, K, scratch != nullptr, wgs);
+  // the LayerNorm-folded epilogues and the row statistics live in the main kernel only: no cutting there
+  const SchedPlan plan = sched_plan(M, N, K, scratch != nullptr && !FOLD, wgs);
   kern<<<dim3((unsigned)(kXcds * wgs)), dim3(256), lds, s>>>(x, w, bias, res, y, M, N, K, epi, plan, scratch, lf);
   e = hipGetLastError();
-  if (e != hipSuccess || !plan.split) return e;
-  e = ensure_dynamic_lds(reinterpret_cast<const void*>(fix), epi_stage, attr_fix);
-  if (e != hipSuccess) return e;
-  fix<<<dim3((unsigned)(kXcds * wgs)), dim3(256), epi_stage, s>>>(scratch, bias, res, y, M, N, epi, plan, lf);
+  if (e != hipSuccess || plan.pieces == 1) return e;
+  const int32_t max_rem = sched_max_rem(plan);
+  gemm_mfma_fixup_kernel<E><<<dim3((unsigned)(kXcds * max_rem * kFixStrips)), dim3(256), 0, s>>>(scratch, bias, res, y, M, N,
+                                                                                                  epi, plan);
   return hipGetLastError();
 }
 

@@ -262,3 +262,19 @@ def test_static_scratch_generation_step_rejects_bad_arguments_before_touching_th
     assert f(*ok_args(B=60000, lens=None)) == -4          # beyond the fixed scratch array
     c32 = cfg(dtype=E.F32)
     assert f(*ok_args(c=C.byref(c32))) == -6
+
+
+def test_linear_with_scratch_rejects_bad_arguments():
+    f = E.lib().energon_linear_with_scratch
+    assert E.energon_linear_scratch_bytes(577, 1024, 1024, E.BF16) == 0        # too few tiles for the persistent kernel
+    assert E.energon_linear_scratch_bytes(577, 1024, 1000, E.BF16) == 0        # invalid shape
+    assert E.energon_linear_scratch_bytes(8428, 5120, 20480, E.F32) == 0
+    need = E.energon_linear_scratch_bytes(3184, 6144, 12288, E.BF16)           # 312 long tiles on 256 workgroups
+    assert need > 0 and need % 256 == 0
+    args = lambda **kw: [kw.get("x", FAKE), FAKE, None, None, FAKE, 3184, 6144, kw.get("K", 12288), E.EPI_BIAS, E.BF16,
+                         kw.get("scratch", FAKE), kw.get("nbytes", need), None]
+    assert f(*args(x=None)) == -1
+    assert f(*args(K=12290)) == -2
+    assert f(*args(scratch=None)) == -1
+    assert f(*args(scratch=FAKE + 16)) == -5
+    assert f(*args(nbytes=need - 1)) == -4
