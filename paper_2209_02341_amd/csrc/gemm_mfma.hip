@@ -141,16 +141,27 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
-// FOLD: the LayerNorm-folded epilogues and the row statistics of the residual epilogue are compiled
-// only into the instantiation that serves them; in the plain one their registers would push
-// accumulators out to scratch memory after every tile.
-template <typename E, bool FOLD>
+// MODE selects what is compiled in, so that each instantiation carries only the registers of the
+// epilogues it serves (compiled all together they push a hundred accumulators out to scratch memory
+// after every tile):
+//   0  the plain epilogues (bias, bias + GeLU, bias + residual);
+//   1  the LayerNorm-folded epilogues (EPI_LNFOLD, EPI_LNFOLD_GELU): row statistics read, no residual;
+//   2  bias + residual with the row statistics of the rounded result written to lf.partial.
+constexpr int kEpiPlain = 0, kEpiFolded = 1, kEpiResidualStats = 2;
+template <typename E, int MODE>
 __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], const E* __restrict__ bias,
                                                      const E* res, E* y, int32_t N, int epi, int64_t mw,
-                                                     int32_t nw, int lane, float* stage, const LnFold& lf) {
+                                                     int32_t nw, int lane, float* stage, const LnFold& lf,
+                                                     float* raw = nullptr) {
+  // raw (plain mode only): the workgroup holds a piece of a tile cut along K; its fp32 sums go, without
+  // any epilogue, to raw[256][256] (row-major, this wavefront's quadrant at the offsets it has in the
+  // tile), through the same staging, 32 bytes per lane and row.
+  constexpr bool fold = MODE == kEpiFolded;
+  constexpr bool stats = MODE == kEpiResidualStats;
+  const bool residual = MODE == kEpiResidualStats || (MODE == kEpiPlain && epi == EPI_BIAS_RESIDUAL);
+  const bool gelu = MODE == kEpiFolded ? epi == EPI_LNFOLD_GELU : (MODE == kEpiPlain && epi == EPI_BIAS_GELU);
   const int lrow = lane & 15, lq = lane >> 4;
   const int rr = lane >> 4, c8 = (lane & 15) * 8;
-  const bool fold = FOLD && (epi == EPI_LNFOLD || epi == EPI_LNFOLD_GELU);
   float bv[8], cv[8];
 #pragma unroll
   for (int q = 0; q < 8; ++q) cv[q] = 0.f;
@@ -174,7 +185,7 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
     // traffic instead of stalling every row of the loop below.
     vec8<E> rpre[16];
     float2 spre[16];
-    if (epi == EPI_BIAS_RESIDUAL) {
+    if (residual && raw == nullptr) {
 #pragma unroll
       for (int it = 0; it < 16; ++it)
         rpre[it] = *reinterpret_cast<const vec8<E>*>(res + (size_t)(mw + pass * 64 + it * 4 + rr) * N + nw + c8);
@@ -198,6 +209,12 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
       const int r = it * 4 + rr;
       const float4 lo = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8]);
       const float4 hi = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8 + 4]);
+      if (MODE == kEpiPlain && raw != nullptr) {
+        float* dst = raw + (size_t)(pass * 64 + r) * 256 + c8;
+        *reinterpret_cast<float4*>(dst) = lo;
+        *reinterpret_cast<float4*>(dst + 4) = hi;
+        continue;
+      }
       float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       const size_t off = (size_t)(mw + pass * 64 + r) * N + nw + c8;
       if (fold) {  // r (v - mu c) + b as two multiply-adds
@@ -208,11 +225,11 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] += bv[q];
       }
-      if (epi == EPI_BIAS_GELU || (FOLD && epi == EPI_LNFOLD_GELU)) {
+      if (gelu) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] = gelu_erf(v[q]);
       }
-      if (epi == EPI_BIAS_RESIDUAL) {
+      if (residual) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] += static_cast<float>(rpre[it][q]);
       }
@@ -220,7 +237,7 @@ __device__ __forceinline__ void store_tile_coalesced(const f32x4 (&acc)[8][8], c
 #pragma unroll
       for (int q = 0; q < 8; ++q) o[q] = static_cast<E>(v[q]);
       __builtin_nontemporal_store(o, reinterpret_cast<vec8<E>*>(y + off));
-      if (FOLD && lf.partial != nullptr) {  // the 16 lanes of this row hold one 128-column segment of it
+      if (stats) {  // the 16 lanes of this row hold one 128-column segment of it
         float s1 = 0.f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) s1 += static_cast<float>(o[q]);
@@ -369,8 +386,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
 // block that shares x and W slabs in that XCD's L2.
 //   raster 0: the tiles in bands of kGroupM row tiles, column by column inside a band, cut in 8 equal
 //             runs, one per XCD (resident block: 8 x 4 tiles);
-//   raster 1: XCD x owns row tiles [x R, (x + 1) R), R = tiles_m / 8, walked column by column (resident
-//             block R x wgs / R), all XCDs moving through the columns of W together, so that a W slab
+//   raster 1: XCD x owns row tiles [x R, (x + 1) R), R = tiles_m / 8, walked in bands of at most
+//             kGroupM rows, column by column inside a band (resident block: min(R, 8) rows x wgs /
+//             min(R, 8) columns), all XCDs moving through the columns of W together, so that a W slab
 //             comes from HBM once and reaches the other seven L2s from the memory-side cache; the
 //             tiles_m % 8 leftover row tiles are dealt column-wise, 1/8 to each XCD, at the end.
 // With pieces = P > 1 the tiles of an XCD beyond its last full round (fewer than wgs) are not run as
@@ -382,7 +400,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_tile_kernel(const E* __
 // shares, the textbook stream-K cut, balances better but starts every workgroup at a different K
 // offset: measured on the tensor-parallel shard's QKV shape it took the L2 hit rate down far enough
 // to make the launch 1.7 times slower than with whole tiles.)  A piece leaves its fp32 accumulators
-// in the caller's scratch, slot tile * P + chunk of its XCD; a second kernel adds the P pieces of
+// (row-major 256 x 256) in the caller's scratch, slot tile * P + chunk of its XCD; a second kernel adds the P pieces of
 // every cut tile in ascending K order and applies the epilogue: deterministic, no atomics, no
 // workgroup waits for another.  The tail of a launch is then a short, well filled round instead of
 // a long, partly empty one: that matters where a tile is long and rounds are few (the
@@ -428,9 +446,13 @@ __host__ __device__ inline XcdShare xcd_share(const SchedPlan& p, int32_t x) {
 __host__ __device__ inline void sched_tile(const SchedPlan& p, int32_t x, int32_t l, int32_t& tm, int32_t& tn) {
   if (p.raster == 1) {
     const int32_t rows = p.tiles_m / kXcds, main_n = rows * p.tiles_n;
-    if (l < main_n) {
-      tn = l / rows;
-      tm = x * rows + (l - tn * rows);
+    if (l < main_n) {   // the XCD's rows in bands of kGroupM, column by column inside a band
+      const int32_t band = l / (kGroupM * p.tiles_n);
+      const int32_t first = band * kGroupM;
+      const int32_t band_m = rows - first < kGroupM ? rows - first : kGroupM;
+      const int32_t r = l - band * kGroupM * p.tiles_n;
+      tn = r / band_m;
+      tm = x * rows + first + (r - tn * band_m);
     } else {
       const int32_t left_rows = p.tiles_m - kXcds * rows;
       const int32_t q = (left_rows * p.tiles_n + kXcds - 1) / kXcds;
@@ -478,7 +500,7 @@ constexpr int kPartFloats = 256 * 256;   // one piece's accumulators
       asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));               \
   } while (0)
 
-template <typename E, int BM, int BN, int WM, int WN, bool FOLD>
+template <typename E, int BM, int BN, int WM, int WN, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* __restrict__ x,
                                                                     const E* __restrict__ w,
                                                                     const E* __restrict__ bias,
@@ -707,77 +729,56 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
     // where every VGPR is spoken for: route the lane id through an ordered asm statement.
     int lane_e = lane;
     asm volatile("" : "+v"(lane_e));
-    if (piece_out != nullptr) {
-      // a piece of a cut tile: the accumulators as they are, 16 bytes per lane and store (1 KiB
-      // contiguous per instruction), in the order [wavefront][i][j][lane].  Stored straight from the
-      // accumulator registers: left to the compiler, all 256 are first copied to VGPRs at once, which
-      // costs the whole kernel spills to scratch memory after every tile.
-      char* dst = reinterpret_cast<char*>(piece_out) + ((size_t)wave * (TM * TN * 64) + lane_e) * sizeof(f32x4);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(dst + (size_t)(i * TN + j) * 1024), "a"(acc[i][j]) : "memory");
-    } else {
-      store_tile_coalesced<E, FOLD>(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
-                                    reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf);
-    }
+    // a piece of a cut tile leaves its raw sums (piece_out != nullptr), everything else its results
+    store_tile_coalesced<E, MODE>(acc, bias, res, y, N, epi, m0 + wm0, n0 + wn0, lane_e,
+                                  reinterpret_cast<float*>(smem) + wave * kEpiWaveFloats, lf,
+                                  piece_out != nullptr ? piece_out + (size_t)wm0 * 256 + wn0 : nullptr);
     // the slab buffers (or the staging rows over them) are reused by the next piece's first loads
     __syncthreads();
   }
 }
 
-// Second kernel of a launch that cut tiles.  A workgroup finishes a strip of 16 rows x 128 columns
-// of one cut tile (the 8 accumulator tiles j = 0..7 of row i of one wavefront's quadrant; 32 strips per
-// tile): every thread adds, in ascending K order, the P pieces of two 16-byte accumulator vectors
-// (all loads issued before the first add), the strip is turned through LDS, and each thread then
-// owns 8 consecutive columns of a row: bias, GeLU / residual in fp32, one rounding, one 16-byte
-// store.  blockIdx.x % 8 is the XCD that wrote the pieces.
-constexpr int kFixStrips = 32;
+// Second kernel of a launch that cut tiles.  A workgroup finishes 16 rows of one cut tile (16 strips
+// per tile): every thread owns 8 consecutive columns of a row, adds the P pieces' sums for them in
+// ascending K order (all loads issued before the first add), applies bias, GeLU / residual in fp32,
+// rounds once and stores 16 bytes.  blockIdx.x % 8 is the XCD that wrote the pieces.
+constexpr int kFixStrips = 16;
 template <typename E>
-__global__ __launch_bounds__(256) void gemm_mfma_fixup_kernel(const float* __restrict__ part,
+__global__ __launch_bounds__(512) void gemm_mfma_fixup_kernel(const float* __restrict__ part,
                                                              const E* __restrict__ bias, const E* res, E* y,
                                                              int64_t M, int32_t N, int epi, SchedPlan plan) {
-  __shared__ float stage[16 * kEpiLd];
   const int32_t xcd = blockIdx.x % kXcds, rest = blockIdx.x / kXcds;
   const int32_t t = rest / kFixStrips, strip = rest % kFixStrips;
   const XcdShare share = xcd_share(plan, xcd);
   if (t >= share.rem) return;
   const int32_t n_chunks = (plan.kt + share.chunk - 1) / share.chunk;
-  const int quad = strip >> 3, i = strip & 7;
-  const int tid = threadIdx.x, lane = tid & 63, jw = tid >> 6;   // this thread: accumulator tiles j = 2 jw, 2 jw + 1
-  const f32x4* src = reinterpret_cast<const f32x4*>(part + ((size_t)xcd * (2 * plan.wgs) + (size_t)t * plan.pieces) * kPartFloats) +
-                     ((size_t)quad * 64 + i * 8 + 2 * jw) * 64 + lane;
-  f32x4 sum[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+  const int tid = threadIdx.x;
+  const int r = strip * 16 + (tid >> 5), c8 = (tid & 31) * 8;   // row and first column inside the tile
+  const float* src = part + ((size_t)xcd * (2 * plan.wgs) + (size_t)t * plan.pieces) * kPartFloats + (size_t)r * 256 + c8;
+  float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int32_t c0 = 0; c0 < n_chunks; c0 += 4) {   // four pieces' loads in flight at a time
-    f32x4 v[4][2];
+    float4 lo[4], hi[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < 4; ++c) {
+      const bool live = c0 + c < n_chunks;
+      const float* p = src + (size_t)(live ? c0 + c : c0) * kPartFloats;
+      lo[c] = *reinterpret_cast<const float4*>(p);
+      hi[c] = *reinterpret_cast<const float4*>(p + 4);
+      if (!live) { lo[c] = make_float4(0.f, 0.f, 0.f, 0.f); hi[c] = lo[c]; }
+    }
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
-        v[c][u] = c0 + c < n_chunks ? src[(size_t)(c0 + c) * (kPartFloats / 4) + u * 64] : f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) sum[u] += v[c][u];
+    for (int c = 0; c < 4; ++c) {
+      v[0] += lo[c].x; v[1] += lo[c].y; v[2] += lo[c].z; v[3] += lo[c].w;
+      v[4] += hi[c].x; v[5] += hi[c].y; v[6] += hi[c].z; v[7] += hi[c].w;
+    }
   }
-#pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) stage[((lane >> 4) * 4 + e) * kEpiLd + (2 * jw + u) * 16 + (lane & 15)] = sum[u][e];
-  __syncthreads();
   int32_t tm, tn;
   sched_tile(plan, xcd, share.dp_rounds * plan.wgs + t, tm, tn);
   int64_t m0 = (int64_t)tm * 256;
   int32_t n0 = tn * 256;
   if (m0 > M - 256) m0 = M - 256;
   if (n0 > N - 256) n0 = N - 256;
-  const int r = tid >> 4, c8 = (tid & 15) * 8;
-  const int64_t m = m0 + (quad >> 1) * 128 + i * 16 + r;
-  const int32_t n = n0 + (quad & 1) * 128 + c8;
-  const float4 lo = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8]);
-  const float4 hi = *reinterpret_cast<const float4*>(&stage[r * kEpiLd + c8 + 4]);
-  float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  const int32_t n = n0 + c8;
   if (bias != nullptr) {
     const vec8<E> b8 = *reinterpret_cast<const vec8<E>*>(bias + n);
 #pragma unroll
@@ -787,7 +788,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_fixup_kernel(const float* __res
 #pragma unroll
     for (int q = 0; q < 8; ++q) v[q] = gelu_erf(v[q]);
   }
-  const size_t off = (size_t)m * N + n;
+  const size_t off = (size_t)(m0 + r) * N + n;
   if (epi == EPI_BIAS_RESIDUAL) {
     const vec8<E> r8 = *reinterpret_cast<const vec8<E>*>(res + off);
 #pragma unroll
@@ -934,24 +935,24 @@ size_t gemm_split_scratch_bytes(int64_t M, int32_t N, int32_t K) {
   return ks > 1 ? (size_t)ks * (size_t)M * N * sizeof(float) : 0;
 }
 
-template <typename E, bool FOLD>
+template <typename E, int MODE>
 static hipError_t launch_sched(const E* x, const E* w, const E* bias, const E* res, E* y, int64_t M, int32_t N,
                                int32_t K, int epi, const LnFold& lf, hipStream_t s, float* scratch) {
   constexpr size_t slabs = 2 * (size_t)(256 + 256) * kChunks * sizeof(uint4);
   constexpr size_t epi_stage = 4 * (size_t)kEpiWaveFloats * sizeof(float);
   constexpr size_t lds = slabs > epi_stage ? slabs : epi_stage;
-  static LdsAttrOnce attr_main;   // per element type and FOLD
-  auto kern = gemm_mfma_sched_kernel<E, 256, 256, 2, 2, FOLD>;
+  static LdsAttrOnce attr_main;   // per element type and MODE
+  auto kern = gemm_mfma_sched_kernel<E, 256, 256, 2, 2, MODE>;
   hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, attr_main);
   if (e != hipSuccess) return e;
   const int32_t wgs = sched_wgs_per_xcd();
   // the LayerNorm-folded epilogues and the row statistics live in the main kernel only: no cutting there
-  const SchedPlan plan = sched_plan(M, N, K, scratch != nullptr && !FOLD, wgs);
+  const SchedPlan plan = sched_plan(M, N, K, scratch != nullptr && MODE == kEpiPlain, wgs);
   kern<<<dim3((unsigned)(kXcds * wgs)), dim3(256), lds, s>>>(x, w, bias, res, y, M, N, K, epi, plan, scratch, lf);
   e = hipGetLastError();
   if (e != hipSuccess || plan.pieces == 1) return e;
   const int32_t max_rem = sched_max_rem(plan);
-  gemm_mfma_fixup_kernel<E><<<dim3((unsigned)(kXcds * max_rem * kFixStrips)), dim3(256), 0, s>>>(scratch, bias, res, y, M, N,
+  gemm_mfma_fixup_kernel<E><<<dim3((unsigned)(kXcds * max_rem * kFixStrips)), dim3(512), 0, s>>>(scratch, bias, res, y, M, N,
                                                                                                   epi, plan);
   return hipGetLastError();
 }
@@ -968,9 +969,11 @@ static hipError_t launch_gemm_mfma(const E* x, const E* w, const E* bias, const 
     return hipErrorInvalidValue;
   if (lf.partial == nullptr && gemm_skinny_takes(M, N, K, epi))
     return launch_gemm_skinny<E>(x, w, bias, res, y, M, N, K, epi, s, split_scratch);
-  if (takes_sched_kernel(M, N, K, res == y))
-    return wants_fold || lf.partial != nullptr ? launch_sched<E, true>(x, w, bias, res, y, M, N, K, epi, lf, s, split_scratch)
-                                               : launch_sched<E, false>(x, w, bias, res, y, M, N, K, epi, lf, s, split_scratch);
+  if (takes_sched_kernel(M, N, K, res == y)) {
+    if (wants_fold) return launch_sched<E, kEpiFolded>(x, w, bias, res, y, M, N, K, epi, lf, s, nullptr);
+    if (lf.partial != nullptr) return launch_sched<E, kEpiResidualStats>(x, w, bias, res, y, M, N, K, epi, lf, s, nullptr);
+    return launch_sched<E, kEpiPlain>(x, w, bias, res, y, M, N, K, epi, lf, s, split_scratch);
+  }
   // A batch of a generation step too large for the few-row kernel, with scratch from the caller: K cut
   // over workgroups until there are enough of them, the parts added by a second kernel.  (Not where only
   // the aliased residual kept the shape from the 256x256 kernel: the scratch was sized for that one.)
