@@ -172,6 +172,27 @@ int energon_layer_forward_profiled(const EnergonLayerConfig* cfg,
                                    void* workspace_dev, size_t workspace_bytes, void* stream,
                                    float* stage_ms_host);
 
+/* ---- a stack whose weights do not fit, or are not kept, in device memory ----------------------
+ * Sec. 4.4 of the paper keeps the layers that do not fit a GPU in other memory and fetches each
+ * over a separate stream while the layer before it computes, checking that the copy has finished
+ * before the layer is used.  One GPU's form of that: the L layers' parameters stay in HOST memory
+ * (pinned, so that the copies run asynchronously), two device slots of one layer each receive them
+ * in turn on `copy_stream`, and `stream` runs layer l from slot l % 2 once an event says its copy has
+ * landed; the copy of layer l + 2 into that slot waits, in turn, for an event recorded behind layer
+ * l.  Both streams must have the same (default) priority.  The result is bit-identical to L calls of
+ * energon_layer_forward on resident weights.
+ *   host_layers [L]  structs of HOST pointers (same layouts as EnergonLayerWeights; NULL biases stay NULL)
+ *   x_packed_dev [T, H] in and out (every layer runs in place)
+ *   slot0_dev, slot1_dev: energon_layer_weights_bytes(cfg) bytes each, 256-byte aligned, distinct
+ *   other arguments as energon_layer_forward.  Creates and destroys four events; returns without
+ *   waiting.  Errors as energon_layer_forward, plus UNSUPPORTED if both streams are the same. */
+size_t energon_layer_weights_bytes(const EnergonLayerConfig* cfg);
+int energon_stack_forward_streamed(const EnergonLayerConfig* cfg, const EnergonLayerWeights* host_layers,
+                                   int32_t L, void* x_packed_dev, int64_t T, const int32_t* cu_seqlens_dev,
+                                   const int32_t* lengths_host, int32_t B, int32_t max_len, void* workspace_dev,
+                                   size_t workspace_bytes, void* slot0_dev, void* slot1_dev, size_t slot_bytes,
+                                   void* stream, void* copy_stream);
+
 /* ---- the stages on their own (same kernels energon_layer_forward launches) ---------- */
 
 /* Row-wise LayerNorm over H features: y = (x-mean)/sqrt(var+eps)*gamma+beta, biased

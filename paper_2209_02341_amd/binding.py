@@ -69,6 +69,10 @@ def lib() -> C.CDLL:
         layer_args = [pcfg, pw, vp, vp, i64, vp, vp, i32, i32, vp, sz, vp]
         l.energon_layer_forward.argtypes = layer_args
         l.energon_layer_forward_profiled.argtypes = layer_args + [C.POINTER(C.c_float)]
+        l.energon_layer_weights_bytes.restype = sz
+        l.energon_layer_weights_bytes.argtypes = [pcfg]
+        l.energon_stack_forward_streamed.argtypes = [pcfg, pw, i32, vp, i64, vp, vp, i32, i32, vp, sz, vp, vp, sz, vp, vp]
+        l.energon_stack_forward_streamed.restype = C.c_int
         l.energon_layernorm.argtypes = [vp, vp, vp, vp, i64, i32, C.c_float, i32, vp]
         l.energon_linear.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp]
         l.energon_linear_scratch_bytes.restype = sz
@@ -225,6 +229,24 @@ def energon_layer_forward_profiled(cfg: LayerConfig, weights: LayerWeights, x_pa
                                                 int(workspace.numel() * workspace.element_size()),
                                                 _stream(stream), ms), "energon_layer_forward_profiled")
     return dict(zip(STAGE_NAMES, (float(v) for v in ms)))
+
+
+def energon_layer_weights_bytes(cfg: LayerConfig) -> int:
+    return int(lib().energon_layer_weights_bytes(C.byref(cfg)))
+
+
+def energon_stack_forward_streamed(cfg: LayerConfig, host_layers: list, x_packed, T: int, cu_seqlens, lengths,
+                                   max_len: int, workspace, slot0, slot1, copy_stream, stream=None) -> None:
+    """host_layers: LayerWeights structs whose pointers are (pinned) HOST addresses.  copy_stream: a raw
+    HIP stream handle (e.g. torch.cuda.Stream().cuda_stream)."""
+    lens = _lengths(lengths)
+    arr = (LayerWeights * len(host_layers))(*host_layers)
+    _check(lib().energon_stack_forward_streamed(C.byref(cfg), arr, len(host_layers), _ptr(x_packed), int(T),
+                                                _ptr(cu_seqlens), _ptr(lens), len(lens), int(max_len),
+                                                _ptr(workspace), int(workspace.numel() * workspace.element_size()),
+                                                _ptr(slot0), _ptr(slot1), int(slot0.numel() * slot0.element_size()),
+                                                _stream(stream), int(copy_stream)),
+           "energon_stack_forward_streamed")
 
 
 def energon_layernorm(x, gamma, beta, y, eps: float, stream=None) -> None:

@@ -376,6 +376,98 @@ int energon_layer_forward(const EnergonLayerConfig* cfg, const EnergonLayerWeigh
   return layer_impl(cfg, w, x, y, T, cu, B, max_len, ws, ws_bytes, static_cast<hipStream_t>(stream), nullptr);
 }
 
+// ---- a stack whose weights stay in host memory ---------------------------------------------------
+namespace {
+struct WeightField { const void* EnergonLayerWeights::*ptr; int kind; };   // kind: elements = 0 H, 1 3A*H, 2 3A, 3 H*A, 4 F*H, 5 F, 6 H*F
+const WeightField kWeightFields[12] = {
+    {&EnergonLayerWeights::ln1_g, 0}, {&EnergonLayerWeights::ln1_b, 0}, {&EnergonLayerWeights::w_qkv, 1},
+    {&EnergonLayerWeights::b_qkv, 2}, {&EnergonLayerWeights::w_o, 3},   {&EnergonLayerWeights::b_o, 0},
+    {&EnergonLayerWeights::ln2_g, 0}, {&EnergonLayerWeights::ln2_b, 0}, {&EnergonLayerWeights::w_fc1, 4},
+    {&EnergonLayerWeights::b_fc1, 5}, {&EnergonLayerWeights::w_fc2, 6}, {&EnergonLayerWeights::b_fc2, 0}};
+
+size_t weight_field_bytes(const EnergonLayerConfig* c, int kind) {
+  const size_t H = c->hidden, A = (size_t)c->n_heads * c->head_dim, F = c->ffn, e = esize(c->dtype);
+  const size_t n[7] = {H, 3 * A * H, 3 * A, H * A, F * H, F, H * F};
+  return n[kind] * e;
+}
+}  // namespace
+
+size_t energon_layer_weights_bytes(const EnergonLayerConfig* cfg) {
+  if (check_cfg(cfg) != ENERGON_OK) return 0;
+  size_t t = 0;
+  for (const auto& f : kWeightFields) t += round256(weight_field_bytes(cfg, f.kind));
+  return t;
+}
+
+int energon_stack_forward_streamed(const EnergonLayerConfig* cfg, const EnergonLayerWeights* host_layers, int32_t L,
+                                   void* x, int64_t T, const int32_t* cu, const int32_t* lengths, int32_t B,
+                                   int32_t max_len, void* ws, size_t ws_bytes, void* slot0, void* slot1,
+                                   size_t slot_bytes, void* stream, void* copy_stream) {
+  if (!host_layers || !slot0 || !slot1) return ENERGON_ERR_NULL;
+  if (L <= 0) return ENERGON_ERR_SHAPE;
+  if (stream == copy_stream) return ENERGON_ERR_UNSUPPORTED;   // nothing could overlap
+  if ((reinterpret_cast<uintptr_t>(slot0) & 255u) || (reinterpret_cast<uintptr_t>(slot1) & 255u) || slot0 == slot1)
+    return ENERGON_ERR_ALIGN;
+  {
+    const EnergonLayerWeights probe = host_layers[0];
+    const int st = check_layer_args(cfg, &probe, x, x, T, cu, lengths, B, max_len, ws, ws_bytes);
+    if (st != ENERGON_OK) return st;
+  }
+  if (slot_bytes < energon_layer_weights_bytes(cfg)) return ENERGON_ERR_CAPACITY;
+  for (int32_t l = 0; l < L; ++l) {
+    const EnergonLayerWeights& w = host_layers[l];
+    if (!w.ln1_g || !w.ln1_b || !w.w_qkv || !w.w_o || !w.ln2_g || !w.ln2_b || !w.w_fc1 || !w.w_fc2) return ENERGON_ERR_NULL;
+  }
+  hipStream_t cs = static_cast<hipStream_t>(stream), xs = static_cast<hipStream_t>(copy_stream);
+  void* slots[2] = {slot0, slot1};
+  hipEvent_t ready[2] = {nullptr, nullptr}, released[2] = {nullptr, nullptr};
+  int st = ENERGON_OK;
+  for (int i = 0; i < 2 && st == ENERGON_OK; ++i)
+    if (hipEventCreateWithFlags(&ready[i], hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&released[i], hipEventDisableTiming) != hipSuccess)
+      st = ENERGON_ERR_HIP;
+  // the copies of layer l into slot l % 2, on the copy stream; fills dev with the device addresses
+  auto enqueue_copy = [&](int32_t l, EnergonLayerWeights* dev) -> int {
+    char* base = static_cast<char*>(slots[l & 1]);
+    size_t off = 0;
+    for (const auto& f : kWeightFields) {
+      const size_t nbytes = weight_field_bytes(cfg, f.kind);
+      const void* src = host_layers[l].*(f.ptr);
+      if (src != nullptr) {
+        HIP_TRY(hipMemcpyAsync(base + off, src, nbytes, hipMemcpyHostToDevice, xs));
+        dev->*(f.ptr) = base + off;
+      } else {
+        dev->*(f.ptr) = nullptr;
+      }
+      off += round256(nbytes);
+    }
+    HIP_TRY(hipEventRecord(ready[l & 1], xs));
+    return ENERGON_OK;
+  };
+  EnergonLayerWeights dev[2];
+  // whatever ran on the compute stream before this call may still read the slots
+  if (st == ENERGON_OK && (hipEventRecord(released[0], cs) != hipSuccess || hipStreamWaitEvent(xs, released[0], 0) != hipSuccess))
+    st = ENERGON_ERR_HIP;
+  if (st == ENERGON_OK) st = enqueue_copy(0, &dev[0]);
+  for (int32_t l = 0; l < L && st == ENERGON_OK; ++l) {
+    if (l + 1 < L) {
+      // slot (l + 1) % 2 was last read by layer l - 1: its copy may start once that layer has finished
+      if (l >= 1 && hipStreamWaitEvent(xs, released[(l + 1) & 1], 0) != hipSuccess) { st = ENERGON_ERR_HIP; break; }
+      st = enqueue_copy(l + 1, &dev[(l + 1) & 1]);
+      if (st != ENERGON_OK) break;
+    }
+    if (hipStreamWaitEvent(cs, ready[l & 1], 0) != hipSuccess) { st = ENERGON_ERR_HIP; break; }
+    st = layer_impl(cfg, &dev[l & 1], x, x, T, cu, B, max_len, ws, ws_bytes, cs, nullptr);
+    if (st == ENERGON_OK && hipEventRecord(released[l & 1], cs) != hipSuccess) st = ENERGON_ERR_HIP;
+  }
+  // an event may be destroyed while work that refers to it is pending: the runtime releases it when that completes
+  for (int i = 0; i < 2; ++i) {
+    if (ready[i]) (void)hipEventDestroy(ready[i]);
+    if (released[i]) (void)hipEventDestroy(released[i]);
+  }
+  return st;
+}
+
 int energon_layer_forward_profiled(const EnergonLayerConfig* cfg, const EnergonLayerWeights* w, const void* x,
                                    void* y, int64_t T, const int32_t* cu, const int32_t* lengths, int32_t B,
                                    int32_t max_len, void* ws, size_t ws_bytes, void* stream, float* stage_ms) {

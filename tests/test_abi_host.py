@@ -278,3 +278,24 @@ def test_linear_with_scratch_rejects_bad_arguments():
     assert f(*args(scratch=None)) == -1
     assert f(*args(scratch=FAKE + 16)) == -5
     assert f(*args(nbytes=need - 1)) == -4
+
+
+def test_streamed_stack_rejects_bad_arguments_before_touching_the_device():
+    f = E.lib().energon_stack_forward_streamed
+    c, w = cfg(), E.LayerWeights(*([FAKE] * 12))
+    lens = np.asarray([3, 2], dtype=np.int32)
+    need = E.energon_layer_weights_bytes(c)
+    assert need >= 2 * (1024 * 3072 + 1024 * 1024 + 2 * 1024 * 4096) and need % 256 == 0
+    assert E.energon_layer_weights_bytes(cfg(head_dim=80)) == 0
+    args = lambda **kw: [C.byref(c), kw.get("w", C.byref(w)), kw.get("L", 1), kw.get("x", FAKE), 5, FAKE, lens.ctypes.data, 2, 4,
+                         FAKE, 1 << 30, kw.get("s0", FAKE), kw.get("s1", FAKE + 4096), kw.get("nbytes", need), None,
+                         kw.get("cs", 1)]
+    assert f(*args(w=None)) == -1
+    assert f(*args(L=0)) == -2
+    assert f(*args(cs=None)) == -6          # copy stream = compute stream
+    assert f(*args(s1=FAKE)) == -5          # the two slots must be distinct
+    assert f(*args(s0=FAKE + 16)) == -5
+    assert f(*args(x=None)) == -1
+    assert f(*args(nbytes=need - 1)) == -4
+    w2 = E.LayerWeights(*([FAKE] * 12)); w2.w_fc2 = None
+    assert f(*args(w=C.byref(w2))) == -1
