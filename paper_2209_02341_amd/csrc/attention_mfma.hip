@@ -18,9 +18,13 @@
 // as both operands agree, so V^T is kept in LDS in the order the accumulator layout dictates:
 // position 8 g + i of a 32-key step holds key 4 g + i (i < 4) or 16 + 4 g + i - 4 of that step,
 // which makes a lane's 8 keys (g = lane / 16) one 16-byte read.
-// K tiles go from global memory straight to LDS (global_load_lds_dwordx4, the swizzle applied on
-// the global side); V is transposed on its way into LDS (key-contiguous rows), two keys per
-// 32-bit store, through registers.
+// K and V tiles go from global memory straight to LDS (global_load_lds_dwordx4, whole 128- or
+// 256-byte row pieces, the swizzle applied on the global side).  Every wavefront then reads back the
+// eight V rows it fetched itself (no barrier needed for that), 16 bytes per lane, and writes them
+// transposed (key-contiguous rows), two keys per 32-bit store, into the V^T tile.  (Fetching V
+// with one key per lane, so that it arrives in the registers ready for that transposition, made
+// every load instruction touch 64 different cache lines for 16 bytes each; the kernel then ran at
+// under 3 TB/s of useful bytes on short sequences, where it is a plain streaming read.)
 #include "common.h"
 
 namespace energon {
@@ -57,8 +61,9 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
   constexpr int KC = D / 8;         // 16-byte chunks per K row
   constexpr int KROWS = 64 / KC;    // K rows moved by one direct-to-LDS instruction (1 KiB)
   constexpr int KDMA = kBKV / KROWS / kAttnWaves;   // such instructions per wavefront and tile
-  constexpr int VLOADS = KC / kAttnWaves;           // 16-byte V chunks staged per thread
-  constexpr int kStage = (kBKV * D * 2 + D * kBKV * 2) / 16;  // uint4 per stage: K tile + V^T tile
+  constexpr int VLOADS = KC / kAttnWaves;           // 16-byte V chunks transposed per thread
+  constexpr int kTile = kBKV * D * 2 / 16;          // uint4 per K, V or V^T tile
+  // LDS: K tile of the even trips, K tile of the odd trips, the V tile as fetched, the V^T tile
   static_assert(KDMA >= 1 && VLOADS >= 1, "head dimension too small for eight wavefronts");
   extern __shared__ uint4 lds[];
 
@@ -112,48 +117,57 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
   uint32_t kcol[KDMA];   // byte offset of the chunk this lane fetches, inside its row
 #pragma unroll
   for (int i = 0; i < KDMA; ++i) kcol[i] = (uint32_t)((ksl ^ kswz<D>((wave * KDMA + i) * KROWS + kr)) * 16);
-  // V transposition (see below): the lane holds 8 consecutive dd of key `lane` of the tile; with
-  // its neighbour (key ^ 1) it forms, per dd, the 32-bit word (even key, odd key).  Even lanes
-  // write dd 0, 2, 4, 6 of the chunk, odd lanes dd 1, 3, 5, 7.  One byte permute builds the word.
-  const int kp = lane >> 1, odd = lane & 1;
+  // V: the wavefront fetches rows 8 w .. 8 w + 7 of the tile (the same row groups as for K, swizzled by
+  // the row's low three bits) and later reads them back itself: the lane takes key 8 w + lane % 8 and,
+  // per read, the chunk c of 8 consecutive dd chosen so that 16 neighbouring lanes cover all 64 banks
+  // (D = 128: the two halves of a row alternate every 8 lanes).  With its neighbour (key ^ 1, same
+  // chunk) it forms, per dd, the 32-bit word (even key, odd key): even lanes write dd 0, 2, 4, 6 of the
+  // chunk, odd lanes dd 1, 3, 5, 7; one byte permute builds the word.
+  uint32_t vcol[KDMA];   // byte offset of the chunk this lane fetches, inside its row
+#pragma unroll
+  for (int i = 0; i < KDMA; ++i) vcol[i] = (uint32_t)((ksl ^ (((wave * KDMA + i) * KROWS + kr) & 7)) * 16);
+  const int vkey = wave * 8 + (lane & 7), odd = lane & 1;
+  const int kp = vkey >> 1;
   const uint32_t vsel = odd ? 0x03020706u : 0x05040100u;   // v_perm_b32 selector, bytes of {partner, own}
+  uint32_t vsrc[VLOADS];     // uint4 index of the read inside the fetched V tile
   uint32_t vdst[VLOADS][4];  // word index of the store inside the V^T tile
 #pragma unroll
-  for (int j = 0; j < VLOADS; ++j)
+  for (int j = 0; j < VLOADS; ++j) {
+    const int c = KC == 16 ? 8 * ((lane >> 3) & 1) + (lane >> 4) + 4 * j : (lane >> 3);
+    vsrc[j] = (uint32_t)(vkey * KC + (c ^ (vkey & 7)));
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int dd = (wave + kAttnWaves * j) * 8 + 2 * e + odd;
+      const int dd = c * 8 + 2 * e + odd;
       // key pair kp = 16 s + 8 h + 2 g + i (keys 32 s + 16 h + 4 g + 2 i, + 1) goes to 16-byte chunk
       // 4 s + g of the row, word 2 h + i of the chunk
       const int chunk = 4 * (kp >> 4) + ((kp >> 1) & 3), word = 2 * ((kp >> 3) & 1) + (kp & 1);
       vdst[j][e] = (uint32_t)(dd * 32 + ((chunk ^ vswz(dd)) * 4) + word);
     }
+  }
 
-  // Tile t+1 is fetched while tile t is consumed: K straight into the other LDS buffer (free since
-  // the barrier that ended the previous trip), V into registers and from there, transposed, into
-  // that buffer after the arithmetic.  The loop starts at t = -1 (fetch tile 0, nothing to
-  // consume); past the end the last tile is fetched again and never used.
+  // Tile t+1 is fetched while tile t is consumed: K into the other K buffer (free since the barrier
+  // that ended the previous trip), V into the one buffer for fetched V tiles (its previous content
+  // was transposed out before that barrier).  After the arithmetic and a barrier (V^T(t) is no longer
+  // read) every wavefront waits for its own loads, transposes its eight V rows into the V^T tile,
+  // and a second barrier publishes K(t+1) and V^T(t+1).  The loop starts at t = -1 (fetch tile 0,
+  // nothing to consume); past the end the last tile is fetched again and never used.
+  uint4* const vraw = lds + 2 * kTile;
+  uint32_t* const vt_words = reinterpret_cast<uint32_t*>(lds + 3 * kTile);
   for (int32_t t = n_tiles > 0 ? -1 : 0; t < n_tiles; ++t) {  // no tile at all: an empty sequence on the padded path
     const int32_t tn = t + 1 < n_tiles ? t + 1 : n_tiles - 1;
-    uint4* ks_next = lds + ((t + 1) & 1) * kStage;
+    uint4* ks_next = lds + ((t + 1) & 1) * kTile;
 #pragma unroll
     for (int i = 0; i < KDMA; ++i) {
       int32_t key = tn * kBKV + (wave * KDMA + i) * KROWS + kr; key = key < len ? key : len - 1;
       __builtin_amdgcn_global_load_lds((attn_gptr_t)(kbytes + ((uint32_t)key * ld_b + kcol[i])),
                                        (attn_lptr_t)(ks_next + (wave * KDMA + i) * 64), 16, 0, 0);
-    }
-    uint4 vreg[VLOADS];
-    {
-      int32_t vkey = tn * kBKV + lane; vkey = vkey < len ? vkey : len - 1;
-      const uint32_t voff = (uint32_t)vkey * ld_b + (uint32_t)wave * 16u;
-#pragma unroll
-      for (int j = 0; j < VLOADS; ++j)
-        vreg[j] = *reinterpret_cast<const uint4*>(vbytes + (voff + (uint32_t)(kAttnWaves * j) * 16u));
+      __builtin_amdgcn_global_load_lds((attn_gptr_t)(vbytes + ((uint32_t)key * ld_b + vcol[i])),
+                                       (attn_lptr_t)(vraw + (wave * KDMA + i) * 64), 16, 0, 0);
     }
     const int32_t k0 = t * kBKV;
     if (t >= 0 && k0 <= wq_last) {  // wavefront-uniform: the tile is not wholly above this wavefront's diagonal
-      const uint4* ks = lds + (t & 1) * kStage;
-      const char* vt = reinterpret_cast<const char*>(ks + kBKV * KC);
+      const uint4* ks = lds + (t & 1) * kTile;
+      const char* vt = reinterpret_cast<const char*>(vt_words);
       f32x4 sacc[4];
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) {
@@ -226,21 +240,21 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
         }
       }
     }
-    {
-      uint32_t* vt = reinterpret_cast<uint32_t*>(ks_next + kBKV * KC);
+    if (t >= 0) __syncthreads();         // V^T(t) is no longer read
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's K and V rows have landed in LDS
+    asm volatile("" ::: "memory");       // the reads below must stay behind that wait
 #pragma unroll
-      for (int j = 0; j < VLOADS; ++j) {
+    for (int j = 0; j < VLOADS; ++j) {
+      const uint4 v = vraw[vsrc[j]];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const uint32_t we = e == 0 ? vreg[j].x : e == 1 ? vreg[j].y : e == 2 ? vreg[j].z : vreg[j].w;
-          // the neighbour lane's word (lane ^ 1 inside each quad: quad_perm [1, 0, 3, 2])
-          const uint32_t p = (uint32_t)__builtin_amdgcn_mov_dpp((int)we, 0xB1, 0xF, 0xF, true);
-          vt[vdst[j][e]] = __builtin_amdgcn_perm(p, we, vsel);
-        }
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t we = e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+        // the neighbour lane's word (lane ^ 1 inside each quad: quad_perm [1, 0, 3, 2])
+        const uint32_t p = (uint32_t)__builtin_amdgcn_mov_dpp((int)we, 0xB1, 0xF, 0xF, true);
+        vt_words[vdst[j][e]] = __builtin_amdgcn_perm(p, we, vsel);
       }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's K rows have landed in LDS
-    __syncthreads();
+    __syncthreads();                     // K(t+1) and V^T(t+1) are complete
   }
 
   float l_tot = l_run + __shfl_xor(l_run, 16, 64);
@@ -262,7 +276,7 @@ template <typename E, int D, bool PADDED>
 static hipError_t launch_d(const E* q, const E* k, const E* v, E* out, const int32_t* cu, int32_t B, int32_t max_len,
                            int32_t nh, hipStream_t s) {
   auto kern = attention_mfma_kernel<E, D, PADDED>;
-  constexpr size_t lds = 2 * (size_t)(kBKV * D * 2 + D * kBKV * 2);
+  constexpr size_t lds = 4 * (size_t)(kBKV * D * 2);   // two K tiles, the fetched V tile, the V^T tile
   static LdsAttrOnce once;
   {
     hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds, once);
