@@ -36,9 +36,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA (fp16: the same)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# Bytes per GEMM launch at the L2 -> fabric boundary (mean of the four GEMMs of a layer), from the
-# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/bench_gpt13b_bf16_hbm_traffic.md.
-GEMM_TRAFFIC_BYTES = {"gpt13b_bf16": 2722e6}
+# Bytes per GEMM launch at the L2 -> fabric boundary (mean of the four GEMMs of a layer, the second
+# kernels of the two launches that cut tiles included), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/bench_gpt13b_bf16_hbm_traffic.md.
+GEMM_TRAFFIC_BYTES = {"gpt13b_bf16": 2481e6}
 
 
 def measure_other_workload(name, steps, warmup, seed, log):

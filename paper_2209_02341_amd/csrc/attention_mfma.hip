@@ -150,19 +150,21 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
   // was transposed out before that barrier).  After the arithmetic and a barrier (V^T(t) is no longer
   // read) every wavefront waits for its own loads, transposes its eight V rows into the V^T tile,
   // and a second barrier publishes K(t+1) and V^T(t+1).  The loop starts at t = -1 (fetch tile 0,
-  // nothing to consume); past the end the last tile is fetched again and never used.
+  // nothing to consume) and ends after the arithmetic of the last tile.
   uint4* const vraw = lds + 2 * kTile;
   uint32_t* const vt_words = reinterpret_cast<uint32_t*>(lds + 3 * kTile);
   for (int32_t t = n_tiles > 0 ? -1 : 0; t < n_tiles; ++t) {  // no tile at all: an empty sequence on the padded path
-    const int32_t tn = t + 1 < n_tiles ? t + 1 : n_tiles - 1;
-    uint4* ks_next = lds + ((t + 1) & 1) * kTile;
+    const bool more = t + 1 < n_tiles;   // workgroup-uniform: there is a tile to fetch
+    if (more) {
+      uint4* ks_next = lds + ((t + 1) & 1) * kTile;
 #pragma unroll
-    for (int i = 0; i < KDMA; ++i) {
-      int32_t key = tn * kBKV + (wave * KDMA + i) * KROWS + kr; key = key < len ? key : len - 1;
-      __builtin_amdgcn_global_load_lds((attn_gptr_t)(kbytes + ((uint32_t)key * ld_b + kcol[i])),
-                                       (attn_lptr_t)(ks_next + (wave * KDMA + i) * 64), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((attn_gptr_t)(vbytes + ((uint32_t)key * ld_b + vcol[i])),
-                                       (attn_lptr_t)(vraw + (wave * KDMA + i) * 64), 16, 0, 0);
+      for (int i = 0; i < KDMA; ++i) {
+        int32_t key = (t + 1) * kBKV + (wave * KDMA + i) * KROWS + kr; key = key < len ? key : len - 1;
+        __builtin_amdgcn_global_load_lds((attn_gptr_t)(kbytes + ((uint32_t)key * ld_b + kcol[i])),
+                                         (attn_lptr_t)(ks_next + (wave * KDMA + i) * 64), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((attn_gptr_t)(vbytes + ((uint32_t)key * ld_b + vcol[i])),
+                                         (attn_lptr_t)(vraw + (wave * KDMA + i) * 64), 16, 0, 0);
+      }
     }
     const int32_t k0 = t * kBKV;
     if (t >= 0 && k0 <= wq_last) {  // wavefront-uniform: the tile is not wholly above this wavefront's diagonal
@@ -240,6 +242,7 @@ __global__ __launch_bounds__(kAttnWaves * 64, 4) void attention_mfma_kernel(cons
         }
       }
     }
+    if (!more) break;                    // the last tile: nothing was fetched, nothing to publish
     if (t >= 0) __syncthreads();         // V^T(t) is no longer read
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's K and V rows have landed in LDS
     asm volatile("" ::: "memory");       // the reads below must stay behind that wait
