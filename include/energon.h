@@ -223,6 +223,16 @@ int energon_linear_with_scratch(const void* x_dev, const void* w_dev, const void
                                 int32_t epilogue, int32_t dtype, void* scratch_dev, size_t scratch_bytes,
                                 void* stream);
 
+/* Host only, no device is touched: replays, for one 16-bit problem shape, how the persistent
+ * contraction kernel deals tiles and pieces of tiles to `workgroups_per_xcd` workgroups on each of
+ * the 8 XCDs (32 on MI355X; other values exercise the arithmetic), with or without scratch, and
+ * checks that every tile and every slab of K is covered exactly once and that the pieces of a cut
+ * tile sit where the second kernel reads them.  Returns 0 if so, a positive code naming the first
+ * violated rule otherwise, -1 if that kernel does not take the shape (fewer than 192 tiles of 256 x
+ * 256, or K not a multiple of 128).  pieces_out (optional): pieces per cut tile, 1 = no cutting. */
+int energon_linear_plan_selfcheck(int64_t M, int32_t N, int32_t K, int32_t workgroups_per_xcd,
+                                  int32_t with_scratch, int32_t* pieces_out);
+
 /* Causal attention of every sequence over its real length, on packed rows.
  *   qkv_dev [T, 3A]  (row t: Q | K | V, head h at columns h*d .. (h+1)*d-1 of each third)
  *   out_dev [T, A];  cu_seqlens_dev [B+1];  max_len >= every sequence length.

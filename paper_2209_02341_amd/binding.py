@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         l.energon_linear_scratch_bytes.argtypes = [i64, i32, i32, i32]
         l.energon_linear_with_scratch.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, vp, sz, vp]
         l.energon_linear_with_scratch.restype = C.c_int
+        l.energon_linear_plan_selfcheck.argtypes = [i64, i32, i32, i32, i32, C.POINTER(i32)]
+        l.energon_linear_plan_selfcheck.restype = C.c_int
         l.energon_attention.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         l.energon_rebuild_qkv.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         l.energon_attention_padded.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
@@ -273,6 +275,14 @@ def energon_linear_with_scratch(x, w, bias, residual, y, epilogue: int, scratch,
     _check(lib().energon_linear_with_scratch(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K,
                                              int(epilogue), _dtype_code(x), _ptr(scratch), nbytes, _stream(stream)),
            "energon_linear_with_scratch")
+
+
+def energon_linear_plan_selfcheck(M: int, N: int, K: int, workgroups_per_xcd: int = 32, with_scratch: bool = True):
+    """(status, pieces): status 0 = the decomposition covers every tile and slab once; -1 = shape not taken."""
+    pieces = C.c_int32(0)
+    st = lib().energon_linear_plan_selfcheck(int(M), int(N), int(K), int(workgroups_per_xcd), int(bool(with_scratch)),
+                                             C.byref(pieces))
+    return int(st), int(pieces.value)
 
 
 def energon_attention(qkv, out, cu_seqlens, B: int, max_len: int, n_heads: int, head_dim: int,

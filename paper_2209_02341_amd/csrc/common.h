@@ -154,6 +154,8 @@ size_t gemm_split_scratch_bytes(int64_t M, int32_t N, int32_t K);
 // the part of the above that belongs to the persistent 256x256 kernel (0 if it does not take the shape
 // or would not cut tiles along K): room for two pieces of 256x256 fp32 accumulators per workgroup
 size_t gemm_sched_scratch_bytes(int64_t M, int32_t N, int32_t K);
+// host-side replay of that kernel's work decomposition for one shape: 0 = every tile and slab covered once
+int gemm_sched_selfcheck(int64_t M, int32_t N, int32_t K, int32_t wgs, int32_t can_split, int32_t* pieces_out);
 hipError_t launch_gemm_bf16(const bf16_t* x, const bf16_t* w, const bf16_t* bias, const bf16_t* res, bf16_t* y,
                             int64_t M, int32_t N, int32_t K, int epi, hipStream_t s, const LnFold* fold = nullptr,
                             float* split_scratch = nullptr);

@@ -587,6 +587,12 @@ int energon_linear_with_scratch(const void* x, const void* w, const void* bias, 
                      need > 0 ? static_cast<float*>(scratch) : nullptr);
 }
 
+int energon_linear_plan_selfcheck(int64_t M, int32_t N, int32_t K, int32_t workgroups_per_xcd, int32_t with_scratch,
+                                  int32_t* pieces_out) {
+  if (M <= 0 || N <= 0 || K <= 0 || K % 64 != 0 || workgroups_per_xcd < 1 || workgroups_per_xcd > 1024) return -1;
+  return gemm_sched_selfcheck(M, N, K, workgroups_per_xcd, with_scratch, pieces_out);
+}
+
 int energon_attention(const void* qkv, void* out, const int32_t* cu, int64_t T, int32_t B, int32_t max_len,
                       int32_t n_heads, int32_t head_dim, int32_t dtype, void* stream) {
   if (!qkv || !out || !cu) return ENERGON_ERR_NULL;

@@ -25,6 +25,8 @@
 //    stores: used with 128x128 tiles for everything the first kernel does not take (small or
 //    ragged-below-one-tile problems, odd slab counts).
 #include "common.h"
+#include <algorithm>
+#include <vector>
 
 namespace energon {
 
@@ -472,6 +474,45 @@ __host__ __device__ inline void sched_tile(const SchedPlan& p, int32_t x, int32_
   }
 }
 
+// The work of workgroup `wg` of XCD `xcd`, in the order it is done: whole tiles first, then pieces of
+// the XCD's cut tiles.  next() yields tile l of the XCD's sequence, the slabs [kb, kb + n) of it, and
+// the scratch slot of the piece inside the XCD's 2 * wgs slots (-1: the whole tile, finished by this
+// workgroup).  Shared by the kernel and the host-side check of the decomposition.
+struct SchedWalker {
+  XcdShare share;
+  int32_t wgs, wg, kt, pieces, n_whole, n_chunks, q_stop, done, q;
+  __host__ __device__ SchedWalker(const SchedPlan& p, int32_t xcd, int32_t wg_) {
+    share = xcd_share(p, xcd);
+    wgs = p.wgs; wg = wg_; kt = p.kt; pieces = p.pieces;
+    if (p.pieces > 1) n_whole = share.dp_rounds;
+    else n_whole = share.n_tiles > wg ? (share.n_tiles - wg + wgs - 1) / wgs : 0;
+    n_chunks = (kt + share.chunk - 1) / share.chunk;   // <= pieces
+    q_stop = share.rem * n_chunks;
+    done = 0;
+    q = wg;
+  }
+  __host__ __device__ bool next(int32_t& l, int32_t& kb, int32_t& n, int32_t& slot) {
+    if (done < n_whole) {
+      l = done * wgs + wg;
+      kb = 0;
+      n = kt;
+      slot = -1;
+      ++done;
+      return true;
+    }
+    if (q < q_stop) {
+      const int32_t c = q / share.rem, t = q - c * share.rem;
+      l = share.dp_rounds * wgs + t;
+      kb = c * share.chunk;
+      n = kt - kb < share.chunk ? kt - kb : share.chunk;
+      slot = t * pieces + c;
+      q += wgs;
+      return true;
+    }
+    return false;
+  }
+};
+
 constexpr int kPartFloats = 256 * 256;   // one piece's accumulators
 
 // The slab loop is written as ordered inline-asm statements so that the issue order is exactly
@@ -522,34 +563,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_sched_kernel(const E* _
   const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
 
   // This workgroup's share: whole tiles first, then its pieces of the XCD's cut tiles.
-  const int32_t xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds;
-  const XcdShare share = xcd_share(plan, xcd);
-  const int32_t kt_all = plan.kt;
-  int32_t n_whole;   // whole tiles of this workgroup
-  if (plan.pieces > 1) n_whole = share.dp_rounds;
-  else n_whole = share.n_tiles > wg ? (share.n_tiles - wg + plan.wgs - 1) / plan.wgs : 0;
-  const int32_t n_chunks = (kt_all + share.chunk - 1) / share.chunk;   // <= plan.pieces
-  const int32_t q_stop = share.rem * n_chunks;
-  int32_t q = wg;   // next piece
+  const int32_t xcd = blockIdx.x % kXcds;
+  SchedWalker walk(plan, xcd, blockIdx.x / kXcds);
 
-  for (int32_t done = 0;; ++done) {
+  for (;;) {
     // ---- next piece of work: tile l of the XCD's sequence, slabs [kb, kb + KT) of it ----
-    int32_t l, kb, KT;
-    float* piece_out = nullptr;   // non-null: the piece does not cover its tile
-    if (done < n_whole) {
-      l = done * plan.wgs + wg;
-      kb = 0;
-      KT = kt_all;
-    } else if (q < q_stop) {
-      const int32_t c = q / share.rem, t = q - c * share.rem;
-      l = share.dp_rounds * plan.wgs + t;
-      kb = c * share.chunk;
-      KT = min(share.chunk, kt_all - kb);
-      piece_out = part + ((size_t)xcd * (2 * plan.wgs) + (size_t)(t * plan.pieces + c)) * kPartFloats;
-      q += plan.wgs;
-    } else {
-      break;
-    }
+    int32_t l, kb, KT, slot;
+    if (!walk.next(l, kb, KT, slot)) break;
+    // non-null: the piece does not cover its tile
+    float* const piece_out = slot < 0 ? nullptr : part + ((size_t)xcd * (2 * plan.wgs) + (size_t)slot) * kPartFloats;
     int32_t tm, tn;
     sched_tile(plan, xcd, l, tm, tn);
     int64_t m0 = (int64_t)tm * BM;
@@ -933,6 +955,76 @@ size_t gemm_split_scratch_bytes(int64_t M, int32_t N, int32_t K) {
   int32_t tile, ks;
   gemm_split_plan(M, N, K, &tile, &ks);
   return ks > 1 ? (size_t)ks * (size_t)M * N * sizeof(float) : 0;
+}
+
+// Host-side check of the decomposition for one shape (what the kernels would do, replayed with the
+// same functions): every tile is either finished whole by exactly one workgroup or cut into pieces
+// whose slab ranges are even, start where the previous one ended and add up to the tile; the pieces of
+// a tile occupy the slots its second-kernel workgroups read, in ascending K order; no slot is used
+// twice or lies outside the XCD's 2 * wgs.  0 if all of that holds, else a positive code naming the
+// first violation; -1 if the 256x256 kernel does not take the shape.
+int gemm_sched_selfcheck(int64_t M, int32_t N, int32_t K, int32_t wgs, int32_t can_split, int32_t* pieces_out) {
+  if (!takes_sched_kernel(M, N, K, false) || wgs < 1) return -1;
+  const SchedPlan p = sched_plan(M, N, K, can_split != 0, wgs);
+  if (pieces_out) *pieces_out = p.pieces;
+  const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+  std::vector<int32_t> covered(tiles, 0);     // slabs covered so far (pieces must arrive in K order per tile)
+  std::vector<int8_t> whole(tiles, 0);
+  for (int32_t x = 0; x < kXcds; ++x) {
+    const XcdShare sh = xcd_share(p, x);
+    std::vector<int8_t> slot_used(2 * (size_t)wgs, 0);
+    // pieces of one tile are produced by different workgroups: collect (tile, kb, n, slot) and sort by kb
+    struct Piece { int64_t tile; int32_t kb, n, slot; };
+    std::vector<Piece> pieces;
+    int64_t seen = 0;
+    for (int32_t wg = 0; wg < wgs; ++wg) {
+      SchedWalker walk(p, x, wg);
+      int32_t l, kb, n, slot;
+      while (walk.next(l, kb, n, slot)) {
+        if (l < 0 || l >= sh.n_tiles) return 1;
+        int32_t tm, tn;
+        sched_tile(p, x, l, tm, tn);
+        if (tm < 0 || tm >= p.tiles_m || tn < 0 || tn >= p.tiles_n) return 2;
+        const int64_t tile = (int64_t)tm * p.tiles_n + tn;
+        if (n <= 0 || (n & 1) || (kb & 1) || kb < 0 || kb + n > p.kt) return 3;
+        if (slot < 0) {
+          if (kb != 0 || n != p.kt || whole[tile] || covered[tile]) return 4;
+          whole[tile] = 1;
+          covered[tile] = p.kt;
+        } else {
+          if (slot >= 2 * wgs || slot_used[slot]) return 5;
+          slot_used[slot] = 1;
+          pieces.push_back({tile, kb, n, slot});
+        }
+        ++seen;
+      }
+    }
+    std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) { return a.tile != b.tile ? a.tile < b.tile : a.kb < b.kb; });
+    for (const Piece& q : pieces) {
+      if (whole[q.tile] || covered[q.tile] != q.kb) return 6;
+      covered[q.tile] += q.n;
+    }
+    // what the second kernel reads: cut tile t of this XCD = tile dp_rounds * wgs + t, slots t * P + c, c ascending
+    const int32_t n_chunks = (p.kt + sh.chunk - 1) / sh.chunk;
+    for (int32_t t = 0; t < sh.rem; ++t) {
+      int32_t tm, tn;
+      sched_tile(p, x, sh.dp_rounds * wgs + t, tm, tn);
+      const int64_t tile = (int64_t)tm * p.tiles_n + tn;
+      int32_t kb = 0;
+      for (int32_t c = 0; c < n_chunks; ++c) {
+        bool found = false;
+        for (const Piece& q : pieces)
+          if (q.slot == t * p.pieces + c) { found = q.tile == tile && q.kb == kb; kb += q.n; break; }
+        if (!found) return 7;
+      }
+      if (kb != p.kt) return 8;
+    }
+    if (sh.rem > wgs || (p.pieces > 1 && sh.rem * p.pieces > 2 * wgs)) return 9;
+    (void)seen;
+  }
+  for (int64_t t = 0; t < tiles; ++t)
+    if (covered[t] != p.kt) return 10;
+  return 0;
 }
 
 template <typename E, int MODE>
