@@ -18,6 +18,8 @@ the timed region.  Prints ONE JSON line:
   streamed_weights  the same step with the L layers' weights kept in pinned host memory and fetched one
              layer ahead on a second stream (the paper's asynchronous layer prefetch, one-GPU form), next to
              the copies alone: bound by the host link
+  hip_graph_replay  the same step recorded once into a HIP graph and replayed: one submission per step
+             instead of a launch per kernel (`value` stays the launch-per-kernel figure)
   other_workloads  the tensor-parallel shard and the heavy-padding workload (each packed and padded:
              the speed-up against the row ratio) and the zero-padding control (whole step against the
              layers alone: what pack + unpack cost when there is nothing to remove), a few steps each
@@ -88,8 +90,15 @@ def measure_other_workload(name, steps, warmup, seed, log):
                 stage[k] += v / (L * n_prof)
             src, dst = dst, src
     tf = flops(lens) / (ms * 1e-3) / 1e12
+    # the same step submitted as one HIP graph (what a serving loop would do where a step is a dozen short launches)
+    graph = run.capture_forward(x_dev, lens, dev_layers)
+    ms_graph = timed(graph.replay, steps, warmup)
+    tf_graph = flops(lens) / (ms_graph * 1e-3) / 1e12
+    del graph
     out["packed"] = {"ms_per_step": ms, "value": T * L / (ms * 1e-3), "tflops": tf,
-                     "pct_bf16_mfma_peak": 100.0 * tf / PEAK_BF16_TFLOPS, "stage_ms_per_layer": stage}
+                     "pct_bf16_mfma_peak": 100.0 * tf / PEAK_BF16_TFLOPS, "stage_ms_per_layer": stage,
+                     "hip_graph_replay": {"ms_per_step": ms_graph, "value": T * L / (ms_graph * 1e-3), "tflops": tf_graph,
+                                          "pct_bf16_mfma_peak": 100.0 * tf_graph / PEAK_BF16_TFLOPS}}
     del run
     torch.cuda.empty_cache()
     full = np.full(B, S, dtype=np.int32)
@@ -112,7 +121,7 @@ def measure_other_workload(name, steps, warmup, seed, log):
         "ms_per_step": ms_pad, "ms_layers_only": ms_layers, "pack_unpack_share": (ms_pad - ms_layers) / ms_pad,
         "tflops": tf_pad, "pct_bf16_mfma_peak": 100.0 * tf_pad / PEAK_BF16_TFLOPS}
     log(f"[bench] {name}: T={T} of {B * S} rows; packed {ms:.3f} ms/step = {tf:.0f} TFLOP/s "
-        f"({100.0 * tf / PEAK_BF16_TFLOPS:.1f} %), padded {ms_pad:.3f} ms -> {ms_pad / ms:.2f}x at row ratio {B * S / T:.2f}; "
+        f"({100.0 * tf / PEAK_BF16_TFLOPS:.1f} %; as one HIP graph {ms_graph:.3f} ms = {100.0 * tf_graph / PEAK_BF16_TFLOPS:.1f} %), padded {ms_pad:.3f} ms -> {ms_pad / ms:.2f}x at row ratio {B * S / T:.2f}; "
         f"control: layers alone {ms_layers:.3f} ms, pack + unpack {100.0 * (ms_pad - ms_layers) / ms_pad:.2f} % of the step")
     del run_p, x_dev, dev_layers
     torch.cuda.empty_cache()
@@ -200,6 +209,19 @@ def main():
     tflops = flops_layer / (ms_layer * 1e-3) / 1e12
     log(f"[bench] packed: {ms_step:.3f} ms/step (median {ms_step_median:.3f}, min {ms_step_min:.3f}), "
         f"{value:,.0f} tokens/s/layer, {tflops:.1f} TFLOP/s")
+
+    # ---- the same step recorded once into a HIP graph and replayed (one submission per step) ----
+    graph = run.capture_forward(x_dev, lens, dev_layers)
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_graph = (time.perf_counter() - t0) / args.steps * 1e3
+    del graph
+    log(f"[bench] as one HIP graph per step: {ms_graph:.3f} ms/step")
 
     # ---- per-stage durations (HIP events on the launch stream), same kernels, same buffers ----
     stage_ms = {k: 0.0 for k in E.STAGE_NAMES}
@@ -442,6 +464,7 @@ def main():
         "stage_ms_per_layer": stage_ms, "stage_tflops": stage_tflops,
         "pack_ms": pack_ms, "unpack_ms": unpack_ms, "hbm": hbm,
         "padded": padded, "paper_attention_path": paper_path, "ln_folded": ln_folded, "decode": decode,
+        "hip_graph_replay": {"ms_per_step": ms_graph, "value": T * L / (ms_graph * 1e-3)},
         "streamed_weights": streamed, "other_workloads": others, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

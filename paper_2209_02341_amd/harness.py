@@ -87,6 +87,23 @@ class PackedRun:
         E.energon_unpack(src, self.cu, T, self.y_padded)
         return self.y_padded
 
+    def capture_forward(self, x_padded: torch.Tensor, lengths: np.ndarray, layers: list) -> "torch.cuda.CUDAGraph":
+        """forward() recorded once into a HIP graph: replay() reruns pack, the layers and unpack on whatever
+        x_padded holds then, for the SAME lengths (they are part of the pack launch's arguments), and
+        leaves the result in y_padded.  The path enqueues kernels only (batches of up to 896 sequences), so
+        nothing in it is refused by a capture.  One eager run on a side stream first: what the library sets
+        once per process (kernel attributes) must not happen inside the capture."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.forward(x_padded, lengths, layers)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.forward(x_padded, lengths, layers)
+        return graph
+
     def forward_folded(self, x_padded: torch.Tensor, lengths: np.ndarray, layers: list) -> torch.Tensor:
         """forward() on FoldedDeviceLayers: the first layer takes its row statistics itself, every
         later one gets them from the epilogue of the layer before."""
