@@ -122,11 +122,12 @@ int energon_workspace_layout(const EnergonLayerConfig* cfg, int64_t tokens, size
  * cu_seqlens_dev[B+1] (exclusive prefix sum of lengths, cu[B] = T) and gathers the valid
  * rows:  x_packed[cu[b]+s, :] = x_padded[b, s, :],  token_idx_dev[cu[b]+s] = b*S + s.
  *   x_padded_dev   [B, S, H]   in
- *   lengths_host   [B]         in, host; copied before return, reusable afterwards.  Up to 896
- *                              sequences: the lengths travel in the launch's argument block, the
- *                              call is one kernel launch and never waits (capturable in a HIP
- *                              graph, with these lengths baked in).  More: they are uploaded with a
- *                              copy from pageable memory, which makes the call wait for `stream`.
+ *   lengths_host   [B]         in, host; read before return, reusable afterwards.  The lengths
+ *                              travel in the launches' argument blocks, 896 per launch: up to 896
+ *                              sequences the call is one kernel launch, beyond that one small scan
+ *                              launch per 896 lengths and the gather.  No copy is enqueued and the
+ *                              call never waits (capturable in a HIP graph, with these lengths
+ *                              baked in).
  *   x_packed_dev   [capacity_tokens, H] out; rows >= T are left untouched
  *   cu_seqlens_dev [B+1] int32 out;  token_idx_dev [capacity_tokens] int32 out (first T)
  *   total_tokens_out           host, optional: T, computed on the host (no device sync)

@@ -134,7 +134,8 @@ struct LensArg { int32_t v[kLensArgMax]; };
 hipError_t launch_pack_scan_rows(const void* x_padded, void* x_packed, const int32_t* lengths_host, int32_t* cu,
                                  int32_t* token_idx, int32_t B, int32_t S, int64_t row_bytes, int64_t T,
                                  hipStream_t s);
-hipError_t launch_scan_lengths(int32_t* cu_seqlens, int32_t B, hipStream_t s);
+// cu_seqlens[0..B] from lengths on the host, any B, in launches that carry 896 lengths each in their argument block
+hipError_t launch_scan_lengths_host(const int32_t* lengths_host, int32_t* cu_seqlens, int32_t B, hipStream_t s);
 hipError_t launch_pack_rows(const void* x_padded, void* x_packed, const int32_t* cu, int32_t* token_idx,
                             int32_t B, int32_t S, int64_t row_bytes, int64_t T, hipStream_t s);
 hipError_t launch_unpack_rows(const void* y_packed, void* y_padded, const int32_t* cu, int32_t B, int32_t S,

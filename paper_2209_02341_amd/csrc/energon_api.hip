@@ -347,10 +347,8 @@ int energon_pack(const void* x_padded, const int32_t* lengths, int32_t B, int32_
     // neither waits for the stream nor reads lengths after it returns)
     HIP_TRY(launch_pack_scan_rows(x_padded, x_packed, lengths, cu, token_idx, B, S, (int64_t)H * esize(dtype), T, s));
   } else {
-    // lengths land in cu[1..B]; the scan kernel turns them into the prefix sums in place.  The copy
-    // from pageable host memory makes the runtime wait until the bytes have left the host buffer.
-    HIP_TRY(hipMemcpyAsync(cu + 1, lengths, sizeof(int32_t) * (size_t)B, hipMemcpyHostToDevice, s));
-    HIP_TRY(launch_scan_lengths(cu, B, s));
+    // more lengths than one argument block holds: a scan launch per 896 of them, then the gather
+    HIP_TRY(launch_scan_lengths_host(lengths, cu, B, s));
     HIP_TRY(launch_pack_rows(x_padded, x_packed, cu, token_idx, B, S, (int64_t)H * esize(dtype), T, s));
   }
   if (total_out) *total_out = T;

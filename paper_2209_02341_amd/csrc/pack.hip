@@ -6,8 +6,9 @@
 // first wavefront of every workgroup scans them with lane shuffles into LDS (a few hundred cycles,
 // hidden behind the other workgroups' row traffic), workgroup 0 also writes cu to global memory,
 // and every wavefront then gathers two consecutive packed rows, finding the first one's sequence by
-// bisection in the LDS copy of cu.  Larger batches upload the lengths, scan them with one
-// wavefront and gather with cu in global memory.  The scatter walks the padded rows and either
+// bisection in the LDS copy of cu.  Larger batches scan the lengths in launches of their own (896 per
+// launch, again from the argument block, each continuing from the previous one's last sum) and gather
+// with cu in global memory.  The scatter walks the padded rows and either
 // copies a packed row or writes zeros.  All row traffic is 16-byte vectors, a wavefront per row, so
 // every access is a full contiguous line; a row moves in batches of eight vectors per lane, all
 // loaded before the first is stored.
@@ -15,24 +16,27 @@
 
 namespace energon {
 
-// cu[1..B] holds the lengths on entry; on exit cu[0] = 0 and cu[b+1] = len[0]+..+len[b].
-// One wavefront: inclusive scan of 64 values by shuffles, carry between chunks.
-__global__ __launch_bounds__(64) void scan_lengths_kernel(int32_t* __restrict__ cu, int32_t B) {
+// Prefix sums of up to kLensArgMax lengths that arrive in the argument block, by one wavefront
+// (inclusive scan of 64 values by shuffles, carry between chunks): cu points at the sum in front of
+// them (written by the launch before this one on the stream, or set to 0 here if these are the first
+// lengths); cu[1..n] receive the sums.
+__global__ __launch_bounds__(64) void scan_lengths_arg_kernel(const LensArg lens, int32_t n, int32_t* __restrict__ cu,
+                                                              int32_t first) {
   const int lane = threadIdx.x;
-  int32_t carry = 0;
-  for (int32_t base = 0; base < B; base += kWave) {
+  int32_t carry = first ? 0 : cu[0];
+  for (int32_t base = 0; base < n; base += kWave) {
     const int32_t i = base + lane;
-    int32_t v = (i < B) ? cu[1 + i] : 0;
+    int32_t v = (i < n) ? lens.v[i] : 0;
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) {
       const int32_t up = __shfl_up(v, o, kWave);
       if (lane >= o) v += up;
     }
     v += carry;
-    if (i < B) cu[1 + i] = v;
+    if (i < n) cu[1 + i] = v;
     carry = __shfl(v, kWave - 1, kWave);
   }
-  if (lane == 0) cu[0] = 0;
+  if (first && lane == 0) cu[0] = 0;
 }
 
 constexpr int kPackWaves = 4;     // wavefronts per workgroup
@@ -137,9 +141,20 @@ static int row_grid(int64_t rows) {
   return (int)(blocks < cap ? (blocks > 0 ? blocks : 1) : cap);
 }
 
-hipError_t launch_scan_lengths(int32_t* cu, int32_t B, hipStream_t s) {
-  scan_lengths_kernel<<<1, kWave, 0, s>>>(cu, B);
-  return hipGetLastError();
+// cu[0..B] from lengths on the host, any B: one small launch per kLensArgMax lengths, each carrying its
+// lengths in its argument block and continuing from the sum the launch before it left (stream order).
+// No copy, so the call never waits and reads lengths_host only before it returns.
+hipError_t launch_scan_lengths_host(const int32_t* lengths_host, int32_t* cu, int32_t B, hipStream_t s) {
+  for (int32_t b0 = 0; b0 < B; b0 += kLensArgMax) {
+    const int32_t n = B - b0 < kLensArgMax ? B - b0 : kLensArgMax;
+    LensArg arg;
+    for (int32_t i = 0; i < n; ++i) arg.v[i] = lengths_host[b0 + i];
+    for (int32_t i = n; i < kLensArgMax; ++i) arg.v[i] = 0;
+    scan_lengths_arg_kernel<<<1, kWave, 0, s>>>(arg, n, cu + b0, b0 == 0 ? 1 : 0);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 static unsigned pack_grid(int64_t T) {
