@@ -123,7 +123,7 @@ PACK_CASES = [
     (32, 512, 5120, None, wl.BF16),     # the 13B-shape batch
     (6, 40, 136, None, wl.F16),
     (896, 3, 64, None, wl.BF16),        # the most sequences whose lengths travel in the launch's arguments
-    (897, 3, 64, None, wl.BF16),        # one more: lengths uploaded, scanned by a kernel of their own
+    (897, 3, 64, None, wl.BF16),        # one more: two scan launches (896 + 1 lengths), then the gather
     (2500, 2, 8, None, wl.F32),
     (33, 700, 5120, None, wl.BF16),     # rows in batches of eight vectors per lane plus a tail (640 = 10 per lane)
     (3, 11, 4104, None, wl.BF16),       # 513 vectors per row: one full batch, one single
